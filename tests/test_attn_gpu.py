@@ -1,0 +1,157 @@
+"""GPU parity: the HIP path (through the C ABI) against the FP64 oracle, element by element."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2603_24517_amd as A
+from paper_2603_24517_amd import workloads as W
+import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+SCALE = 1.0 / math.sqrt(128)
+
+# B, Hq, Hkv, Sq, Skv : several tiles, ragged tails, every head-packing factor, Sq != Skv
+SHAPES = [
+    (1, 1, 1, 1, 1), (1, 1, 1, 1, 70), (1, 1, 1, 33, 1), (1, 2, 2, 64, 64), (2, 2, 2, 100, 77),
+    (1, 2, 2, 300, 200), (1, 1, 1, 257, 513), (2, 4, 4, 512, 512), (1, 3, 3, 129, 640),
+    (1, 2, 1, 200, 260), (1, 4, 1, 150, 150), (2, 8, 1, 70, 333), (1, 8, 2, 96, 96),
+    (1, 3, 1, 90, 190), (1, 6, 2, 130, 65), (1, 16, 1, 40, 129), (1, 12, 3, 65, 64),
+    (1, 1, 1, 700, 130), (1, 4, 2, 31, 1000),
+]
+
+
+@pytest.mark.parametrize("causal", [False, True], ids=["full", "causal"])
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_small_shapes_full_compare(shape, causal):
+    B, Hq, Hkv, Sq, Skv = shape
+    q, k, v = U.rand_qkv(B, Hq, Hkv, Sq, Skv, seed=hash(shape) % 10000)
+    print(f"case shape={shape} causal={causal}", flush=True)
+    U.check_full(q, k, v, causal, SCALE, what=f"{shape} causal={causal}")
+
+
+@pytest.mark.parametrize("q_mul", [4.0, 16.0])
+@pytest.mark.parametrize("causal", [False, True])
+def test_peaked_softmax(q_mul, causal):
+    """Large scores: the running maximum keeps moving and the accumulator is rescaled often."""
+    q, k, v = U.rand_qkv(1, 2, 2, 384, 448, seed=77, q_mul=q_mul)
+    U.check_full(q, k, v, causal, SCALE, what=f"q_mul={q_mul}")
+
+
+def test_sorted_keys_force_rescale_every_block():
+    """Keys ordered by increasing score for every query: the maximum rises in every block."""
+    torch.manual_seed(5)
+    S = 512
+    q = torch.ones(1, 64, 1, 128) * 0.5
+    ramp = torch.linspace(-4.0, 4.0, S).view(1, S, 1, 1)
+    k = (ramp * torch.ones(1, S, 1, 128)).to(torch.bfloat16)
+    v = torch.randn(1, S, 1, 128).to(torch.bfloat16)
+    U.check_full(q.to(torch.bfloat16), k, v, False, 0.5, what="sorted keys")
+
+
+@pytest.mark.parametrize("scale", [0.0, 1.0, 0.01])
+def test_scales(scale):
+    q, k, v = U.rand_qkv(1, 2, 2, 130, 140, seed=11)
+    q = (q.float() * 0.25).to(torch.bfloat16)
+    for causal in (False, True):
+        U.check_full(q, k, v, causal, scale, what=f"scale={scale}")
+
+
+def test_empty_rows_when_sq_gt_skv():
+    q, k, v = U.rand_qkv(1, 2, 2, 300, 40, seed=3)
+    o, lse = U.run_gpu(q, k, v, True, SCALE)
+    assert np.all(lse[:, :, :260] == -np.inf) and np.all(o[:, :260] == 0.0)
+    assert np.all(np.isfinite(lse[:, :, 260:]))
+    U.check_full(q, k, v, True, SCALE, what="empty rows")
+
+
+# ---- the definition's invariants, re-run on the GPU path -----------------------------------------
+def test_constant_v_gpu():
+    q, k, v = U.rand_qkv(1, 4, 2, 200, 300, seed=21)
+    c = torch.randn(1, 1, 2, 128).to(torch.bfloat16)
+    v = c.expand(1, 300, 2, 128).contiguous()
+    for causal in (False, True):
+        o, _ = U.run_gpu(q, k, v, causal, SCALE)
+        want = c.double().numpy()[:, :, np.repeat(np.arange(2), 2), :]
+        assert np.abs(o - want).max() <= 2e-2
+
+
+def test_zero_q_gives_prefix_mean_gpu():
+    _, k, v = U.rand_qkv(1, 2, 2, 150, 150, seed=22)
+    q = torch.zeros(1, 150, 2, 128, dtype=torch.bfloat16)
+    o, lse = U.run_gpu(q, k, v, True, SCALE)
+    vd = v.double().numpy()
+    csum = np.cumsum(vd, axis=1) / np.arange(1, 151).reshape(1, -1, 1, 1)
+    assert np.abs(o - csum).max() <= 2e-2
+    assert np.abs(lse - np.log(np.arange(1, 151))).max() <= 1e-3
+    o, lse = U.run_gpu(q, k, v, False, SCALE)
+    assert np.abs(o - vd.mean(axis=1, keepdims=True)).max() <= 2e-2
+    assert np.abs(lse - math.log(150)).max() <= 1e-3
+
+
+def test_causal_row0_is_v0_gpu():
+    q, k, v = U.rand_qkv(2, 2, 2, 128, 128, seed=23)
+    o, lse = U.run_gpu(q, k, v, True, SCALE)
+    assert np.array_equal(o[:, 0], v[:, 0].double().numpy())     # p = 1 exactly, V is BF16 already
+    s00 = SCALE * (q[:, 0].double() * k[:, 0].double()).sum(-1).numpy()
+    assert np.abs(lse[:, :, 0] - s00).max() <= 1e-3
+
+
+def test_gqa_equals_repeated_mha_gpu():
+    q, k, v = U.rand_qkv(1, 8, 2, 160, 200, seed=24)
+    o, lse = U.run_gpu(q, k, v, True, SCALE)
+    k2, v2 = k.repeat_interleave(4, dim=2), v.repeat_interleave(4, dim=2)
+    o2, lse2 = U.run_gpu(q, k2, v2, True, SCALE)
+    assert np.abs(o - o2).max() <= 2e-2 and np.abs(lse - lse2).max() <= 1e-3
+
+
+def test_split_merge_gpu():
+    q, k, v = U.rand_qkv(1, 2, 2, 100, 320, seed=25)
+    o, lse = U.run_gpu(q, k, v, False, SCALE)
+    o1, l1 = U.run_gpu(q, k[:, :128].contiguous(), v[:, :128].contiguous(), False, SCALE)
+    o2, l2 = U.run_gpu(q, k[:, 128:].contiguous(), v[:, 128:].contiguous(), False, SCALE)
+    tot = np.logaddexp(l1, l2)
+    w1 = np.exp(l1 - tot).transpose(0, 2, 1)[..., None]
+    w2 = np.exp(l2 - tot).transpose(0, 2, 1)[..., None]
+    assert np.abs(lse - tot).max() <= 1e-3
+    assert np.abs(o - (w1 * o1 + w2 * o2)).max() <= 2e-2
+
+
+def test_deterministic_and_stream_gpu():
+    q, k, v = U.rand_qkv(2, 4, 2, 333, 333, seed=26)
+    o1, l1 = U.run_gpu(q, k, v, True, SCALE)
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        o2, l2 = U.run_gpu(q, k, v, True, SCALE, stream=s.cuda_stream)
+    assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
+
+
+def test_attention_wrapper_gpu():
+    q, k, v = U.rand_qkv(1, 2, 2, 64, 64, seed=27)
+    o, lse = A.attention(q.cuda(), k.cuda(), v.cuda(), causal=True)
+    o_ref, lse_ref = oracle.attn_ref(q, k, v, True, SCALE)
+    U.compare(o.cpu().double().numpy(), lse.cpu().double().numpy(), o_ref, lse_ref, "wrapper")
+
+
+# ---- the benchmark configurations ---------------------------------------------------------------------
+def test_cfg1_full():
+    w = W.WORKLOADS[W.SMALL]
+    q, k, v = W.make_qkv(w)
+    r = U.check_full(q, k, v, w.causal, w.scale, what=w.name)
+    print(w.name, r, flush=True)
+
+
+BIG = [n for n in W.WORKLOADS if n != W.SMALL]
+
+
+@pytest.mark.parametrize("name", BIG)
+def test_configs_sampled_rows(name):
+    """Full-size launch (the one bench.py times); a stratified sample of rows checked one by one."""
+    w = W.WORKLOADS[name]
+    print(f"case {name}", flush=True)
+    q, k, v = W.make_qkv(w)
+    rows = W.sample_rows(w, 1536)
+    r = U.check_rows(q, k, v, rows, w.causal, w.scale, what=name)
+    print(name, r, flush=True)
