@@ -1,0 +1,148 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused attention forward on one MI355X.
+
+A "step" is one pass of the whole hot path (one attn_fwd launch) over one batch of seeded
+synthetic input that is already resident in HBM.  Metric: forward TFLOPS counted as
+4*B*Hq*Sq*Skv*D (halved for causal), and the fraction of the dense BF16 MFMA peak.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--all]
+
+Prints ONE JSON line (with --all: one line per workload, the headline workload last).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import paper_2603_24517_amd as A                       # noqa: E402
+from paper_2603_24517_amd import workloads as W        # noqa: E402
+
+PEAK_BF16_TFLOPS = 2516.6      # MI355X dense BF16 MFMA: 256 CU x 4 SIMD x 1024 FLOP/clk x 2.4 GHz
+METRIC = "attention fwd TFLOPS (BF16, D=128) and % of MI355X dense BF16 MFMA peak"
+
+
+def measured_traffic(name):
+    """HBM bytes per launch recorded from rocprofv3 counter runs (profiles/hbm_traffic.json), or None."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if not os.path.exists(path):
+        return None
+    with open(path) as f:
+        return json.load(f).get(name, {}).get("bytes_per_launch")
+
+
+def cpu_baseline(w, q, k, v, o_gpu, lse_gpu, budget_s=12.0):
+    """Time the FP64 oracle (as it stands) on a bounded row sample and check the GPU output on it."""
+    import oracle
+    rows_all = W.sample_rows(w, 16384)
+    qd, kd, vd = q.double().numpy(), k.double().numpy(), v.double().numpy()
+    pilot = rows_all[:: max(1, len(rows_all) // 256)][:256]
+    t0 = time.perf_counter()
+    oracle.attn_ref_rows(qd, kd, vd, pilot, w.causal, w.scale)
+    dt = max(time.perf_counter() - t0, 1e-4)
+    n = int(min(len(rows_all), max(256, budget_s / dt * len(pilot))))
+    rows = rows_all[:: max(1, len(rows_all) // n)][:n]
+    t0 = time.perf_counter()
+    o_ref, lse_ref = oracle.attn_ref_rows(qd, kd, vd, rows, w.causal, w.scale)
+    dt = time.perf_counter() - t0
+    i = rows[:, 2].astype(np.int64)
+    nvalid = np.minimum(w.Skv, i + 1 + w.Skv - w.Sq) if w.causal else np.full_like(i, w.Skv)
+    flops = 4.0 * float(nvalid.clip(min=0).sum()) * w.D          # work the oracle really did
+    b, h = rows[:, 0], rows[:, 1]
+    og = o_gpu[b, i, h].double().cpu().numpy()
+    lg = lse_gpu[b, h, i].double().cpu().numpy()
+    err = np.abs(og - o_ref)
+    dl = np.abs(lg - lse_ref) / np.maximum(1.0, np.abs(lse_ref))
+    base = {"value": flops / dt * 1e-12, "unit": "TFLOPS", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"{len(rows)} stratified query rows of {w.name}, every valid key, FP64, {dt:.1f} s"}
+    parity = {"rows": int(len(rows)), "o_max_abs": float(err.max()), "o_mean_abs": float(err.mean()),
+              "lse_rel_max": float(dl.max()),
+              "pass": bool(err.max() <= 2e-2 and err.mean() <= 2e-3 and dl.max() <= 1e-3)}
+    return base, parity
+
+
+def run_workload(name, steps, warmup, with_cpu, repeats=1):
+    w = W.WORKLOADS[name]
+    dev = torch.device("cuda:0")
+    q, k, v = W.make_qkv(w)
+    qd, kd, vd = q.to(dev), k.to(dev), v.to(dev)
+    o = torch.empty_like(qd)
+    lse = torch.empty((w.B, w.Hq, w.Sq), dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        rc = A.attn_fwd(qd, kd, vd, o, lse, w.B, w.Hq, w.Hkv, w.Sq, w.Skv, w.D, w.causal, w.scale,
+                        stream.cuda_stream)
+        if rc != 0:
+            raise A.AttnError(rc)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    wall, dev_ms = [], []
+    for _ in range(repeats):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record(stream)              # HIP events on the very stream the kernel is launched on
+        for _ in range(steps):
+            step()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        wall.append((time.perf_counter() - t0) * 1e3 / steps)
+        dev_ms.append(e0.elapsed_time(e1) / steps)
+    ms = float(np.mean(wall))
+    kms = float(np.mean(dev_ms))
+    tflops = w.flops / (ms * 1e-3) * 1e-12
+    ktflops = w.flops / (kms * 1e-3) * 1e-12
+    out = {
+        "metric": METRIC, "value": tflops, "unit": "TFLOPS", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "pct_of_peak": 100.0 * tflops / PEAK_BF16_TFLOPS,
+        "config": {"workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "Sq": w.Sq, "Skv": w.Skv, "D": w.D,
+                   "causal": w.causal, "q_mul": w.q_mul, "v_dist": w.v_dist, "seed": w.seed,
+                   "flops_per_step": w.flops},
+        "roofline": {"bound": "mfma", "achieved": ktflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": ktflops / PEAK_BF16_TFLOPS, "traffic": measured_traffic(w.name),
+                     "kernel": "attn_fwd_kernel", "kernel_ms": kms,
+                     "algorithmic_bytes": w.algorithmic_bytes},
+    }
+    if repeats > 1:
+        out["ms_std"] = float(np.std(dev_ms))
+    if with_cpu:
+        out["cpu_baseline"], out["parity"] = cpu_baseline(w, q, k, v, o, lse)
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default=W.HEADLINE, choices=sorted(W.WORKLOADS))
+    ap.add_argument("--all", action="store_true", help="every workload, 10 repeats of --steps each")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1")
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; there is no CPU path")
+    A.load()
+    if args.all:
+        names = [n for n in W.WORKLOADS if n != W.HEADLINE] + [W.HEADLINE]
+        for n in names:
+            steps = max(3, min(args.steps, 30))
+            print(json.dumps(run_workload(n, steps, min(args.warmup, 10), not args.no_cpu, repeats=10)), flush=True)
+    else:
+        print(json.dumps(run_workload(args.workload, args.steps, args.warmup, not args.no_cpu)), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -8,7 +8,8 @@ import ctypes
 import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libattn_mi355x.so")
+# ATTN_MI355X_LIB points at another build of the same library (kernel experiments); default: in-tree build
+LIB_PATH = os.environ.get("ATTN_MI355X_LIB") or os.path.join(_HERE, "libattn_mi355x.so")
 
 ATTN_OK = 0
 ATTN_E_NULL = -1
