@@ -20,17 +20,18 @@
 //     lane-local multiplies.
 //
 // A workgroup is 8 wavefronts (256 query rows) sharing one K/V block stream:
-// tiles go from global memory straight into double-buffered, XOR-swizzled LDS
-// (global_load_lds_dwordx4).  For grouped-query attention the 256 rows are
-// PACK heads of one K/V group x 256/PACK positions, so one K/V tile in LDS
-// serves several query heads.
+// tiles go from global memory straight into three XOR-swizzled LDS stages
+// (global_load_lds_dwordx4), requested two iterations before use.  For
+// grouped-query attention the 256 rows are PACK heads of one K/V group x
+// 256/PACK positions, so one K/V tile in LDS serves several query heads.
 //
-// The two wavefronts that share a SIMD run half an iteration apart: while one
-// issues the 32 MFMAs of "S(j+1) = K(j+1) Q^T ; O += V(j)^T P(j)^T" the other
-// runs the softmax VALU work of its own block, and a workgroup barrier ends
-// each half.  This keeps the matrix pipe and the vector ALU busy at the same
+// The key-block loop is software-pipelined three deep inside every wavefront:
+// iteration j issues the MFMAs of O += P(j) V(j) and S(j+2) = K(j+2) Q^T while
+// its vector instructions turn S(j+1) into P(j+1).  The two instruction kinds
+// are independent within an iteration and are interleaved (one MFMA, its LDS
+// reads, a few VALU), so the matrix pipe and the vector ALU run at the same
 // time (the paper's section 2.2 describes the same need, met on its hardware
-// by specialised warps).
+// by specialised warps), with one workgroup barrier per iteration.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <math.h>
@@ -49,7 +50,6 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 #define LDS_AS __attribute__((address_space(3)))
-#define GLB_AS __attribute__((address_space(1)))
 
 constexpr int HD = 128;              // head dimension
 constexpr int BN = 64;               // keys per K/V block
@@ -61,25 +61,15 @@ constexpr int TILE_BYTES = BN * ROW_BYTES;
 constexpr int NSTAGE = 3;                   // K/V tiles in flight: requested two iterations ahead
 constexpr int V_BASE = NSTAGE * TILE_BYTES; // K stages first, V stages after them
 constexpr int LDS_BYTES = 2 * NSTAGE * TILE_BYTES;
-// The running maximum is only raised when a row's block maximum exceeds it by
-// more than this many powers of two; until then probabilities are formed
-// against the stale maximum (any reference point gives the same softmax) and
-// stay below 2^RESCALE_SLACK.
-constexpr float RESCALE_SLACK = 8.0f;
 // Largest partial row sum (16 probabilities of one lane) the fast softmax path accepts: probabilities
 // stay below 2^14 relative to the reference maximum, far inside BF16 / FP32 range.
 constexpr float P_SUM_LIMIT = 16384.0f;
 #ifndef MAT_PREFETCH
-#define MAT_PREFETCH 4
+#define MAT_PREFETCH 4               // LDS reads run this many MFMAs ahead of their consumer
 #endif
 constexpr int WAIT_VMCNT0 = 0x0F70;  // s_waitcnt vmcnt(0), other counters untouched
 constexpr int WAIT_VMCNT4 = 0x0F74;  // s_waitcnt vmcnt(4): all but the 4 most recent loads have landed
-
-__device__ __forceinline__ void phase_barrier() {
-    __builtin_amdgcn_sched_barrier(0);
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_sched_barrier(0);
-}
+constexpr int WAIT_VMCNT8 = 0x0F78;  // s_waitcnt vmcnt(8)
 
 struct Params {
     const __bf16 *q, *k, *v;
@@ -108,51 +98,37 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
     bf16x2 p = __builtin_convertvector((f32x2){a, b}, bf16x2);   // v_cvt_pk_bf16_f32, nearest even
     return __builtin_bit_cast(uint32_t, p);
 }
-// 16 bytes per lane from global memory straight into LDS: lane L's data lands at lds_base + 16*L.
-// Issued as inline assembly so that the compiler's counter bookkeeping does not make every later
-// LDS read wait for it; the caller waits with s_waitcnt vmcnt(0) before the barrier that publishes
-// the tile.
-__device__ __forceinline__ void lds_dma16(const unsigned char *base, uint32_t voffset, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :
-                 : "s"(lds_base), "v"(voffset), "s"(base)
-                 : "memory");
-}
 __device__ __forceinline__ float max3(float a, float b, float c) {
     float r;
     asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
     return r;
 }
-// Order of the matrix half: LDS reads run PREFETCH MFMAs ahead of the MFMA that consumes them.
-// (A PV MFMA takes two transposing 8-byte reads, a QK MFMA one 16-byte read.)
-template <int SLOT>
-__device__ __forceinline__ void schedule_matrix_slot() {
-    constexpr int MFMA = 0x008, DS_READ = 0x100, NEXT = SLOT + MAT_PREFETCH;
-    __builtin_amdgcn_sched_group_barrier(MFMA, 1, 0);
-    // even slots (PV) take two transposing 8-byte reads, odd slots (QK) one 16-byte read
-    if constexpr (NEXT < 32 && (NEXT & 1) == 0) __builtin_amdgcn_sched_group_barrier(DS_READ, 2, 0);
-    if constexpr (NEXT < 32 && (NEXT & 1) == 1) __builtin_amdgcn_sched_group_barrier(DS_READ, 1, 0);
-    if constexpr (SLOT + 1 < 32) schedule_matrix_slot<SLOT + 1>();
-}
-__device__ __forceinline__ void schedule_matrix_half() {
-    constexpr int DS_READ = 0x100;
-    __builtin_amdgcn_sched_group_barrier(DS_READ, (MAT_PREFETCH / 2) * 3 + (MAT_PREFETCH & 1) * 2, 0);
-    schedule_matrix_slot<0>();
-}
-// Experiment switches (product build: one barrier per iteration, no priority change).
-#ifdef ATTN_TWO_BARRIERS
-#define MID_BARRIER() PHASE_BARRIER()
-#else
-#define MID_BARRIER() __builtin_amdgcn_sched_barrier(0)
+// 16 bytes per lane from global memory straight into LDS: lane L's data lands at lds_base + 16*L.
+// Issued as inline assembly so that the compiler's counter bookkeeping does not make every later
+// LDS read wait for it; the caller waits with s_waitcnt vmcnt(n) before the barrier that publishes
+// the tile.
+__device__ __forceinline__ void lds_dma16(const unsigned char *base, uint32_t voffset, uint32_t lds_base) {
+#ifdef ABL_NO_DMA
+    return;
 #endif
-#ifdef ATTN_MAT_PRIO
-#define MAT_PRIO(x) __builtin_amdgcn_s_setprio((x) ? ATTN_MAT_PRIO : 0)
-#else
-#define MAT_PRIO(x) do { } while (0)
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_base), "v"(voffset), "s"(base)
+                 : "memory");
+}
+// Keeps the instruction that produces x at this point of the program order (no code is emitted).
+#define PIN(x) asm volatile("" : "+v"(x))
+__device__ __forceinline__ void wg_barrier() {
+#ifdef ABL_NO_BARRIER
+    return;
 #endif
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+}
 
 #ifdef ATTN_TRACE
-// Debug build only: per-wavefront clock stamps around every phase barrier of one workgroup.
+// Debug build only: clock stamps of one workgroup's wavefronts at the start and end of the block loop.
 __device__ unsigned long long g_trace[NWAVES][1024];
 __device__ __forceinline__ void trace_mark(int &n) {
     if (blockIdx.x == ATTN_TRACE && n < 1024) {
@@ -161,30 +137,10 @@ __device__ __forceinline__ void trace_mark(int &n) {
         ++n;
     }
 }
-#define TRACE_ALWAYS() do { __builtin_amdgcn_sched_barrier(0); trace_mark(trace_n); __builtin_amdgcn_sched_barrier(0); } while (0)
-#ifdef ATTN_TRACE_LIGHT
-#define PHASE_BARRIER() phase_barrier()
-#define TRACE_POINT() do { } while (0)
+#define TRACE_MARK() do { __builtin_amdgcn_sched_barrier(0); trace_mark(trace_n); __builtin_amdgcn_sched_barrier(0); } while (0)
 #else
-#define PHASE_BARRIER() do { __builtin_amdgcn_sched_barrier(0); trace_mark(trace_n); __builtin_amdgcn_sched_barrier(0); \
-        phase_barrier(); trace_mark(trace_n); __builtin_amdgcn_sched_barrier(0); } while (0)
-#define TRACE_POINT() TRACE_ALWAYS()
+#define TRACE_MARK() do { } while (0)
 #endif
-#else
-#define PHASE_BARRIER() phase_barrier()
-#define TRACE_POINT() do { } while (0)
-#define TRACE_ALWAYS() do { } while (0)
-#endif
-
-// Everything one wavefront keeps across the key-block loop.
-struct WaveState {
-    bf16x8 qf[8];        // Q^T operand: query lane%32, d = 16*s + 8*(lane/32) .. +7
-    f32x16 s[2];         // S^T of the block in flight: two 32-key tiles
-    uint32_t pb[2][8];   // P^T of the previous block, BF16 pairs (the PV operand)
-    f32x16 acc[4];       // O^T accumulator: four 32-d tiles
-    float m;             // running maximum in log2 units (score * scale * log2 e)
-    float l;             // this lane's share of the running sum
-};
 
 template <bool CAUSAL>
 __global__ __launch_bounds__(NTHREADS) void attn_fwd_kernel(const Params p)
@@ -215,44 +171,50 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_kernel(const Params p)
     const int q0 = tile * p.tile_pos + (wave / p.pack) * 32;   // first query row of this wave
     const int off = p.Skv - p.Sq;                               // causal: key j valid iff j <= i + off
 
-    // ---- block counts: nblk for the workgroup (barriers), n_w computed by
-    // this wave, of which the first n_unm need no mask.
+    // ---- block counts: nblk for the workgroup (one barrier each); of these the
+    // first n_unm need no mask for any row of this wavefront; nload of them are
+    // full tiles.
     int nblk = (p.Skv + BN - 1) / BN;
-    int n_w, n_unm = p.Skv / BN;
+    int n_unm = p.Skv / BN;
     if (CAUSAL) {
         const int qlast = min(tile * p.tile_pos + p.tile_pos, p.Sq) - 1;
         const int klast = qlast + off;
         nblk = klast < 0 ? 0 : min(nblk, klast / BN + 1);
-        const int klast_w = q0 + 31 + off;
-        n_w = klast_w < 0 ? 0 : min(nblk, klast_w / BN + 1);
         const int kfirst_w = q0 + off + 1;          // number of keys valid for every row of the wave
         n_unm = min(n_unm, kfirst_w <= 0 ? 0 : kfirst_w / BN);
-    } else {
-        n_w = nblk;
     }
-    n_unm = min(n_unm, n_w);
-    const int nload = min(nblk, p.Skv / BN);    // blocks below this index are full tiles inside the walk
+    n_unm = min(n_unm, nblk);
+    const int nload = min(nblk, p.Skv / BN);
 
 #ifdef ATTN_TRACE
     int trace_n = 0;
 #endif
-    WaveState w;
+    // ---- everything the wavefront keeps across the key-block loop
+    bf16x8 qf[8];          // Q^T operand: query lane%32, d = 16*s + 8*(lane/32) .. +7
+    f32x16 sa[2], sb[2];   // S^T of two blocks in flight (two 32-key tiles each): the softmax consumes one
+                           // while the MFMAs fill the other
+    uint32_t pb[2][8];     // P^T of the block whose PV product comes next, BF16 pairs
+    f32x16 acc[4];         // O^T accumulator: four 32-d tiles
+    float m = -INFINITY;   // running maximum in log2 units (score * scale * log2 e)
+    float l = 0.0f;        // this lane's share of the running sum (its 16 of every 32 keys)
     {
         const int qrow = min(q0 + l32, p.Sq - 1);
         const __bf16 *qp = p.q + ((size_t)((size_t)b * p.Sq + qrow) * p.Hq + head) * HD + 8 * hh;
 #pragma unroll
-        for (int s = 0; s < 8; ++s) w.qf[s] = *(const bf16x8 *)(qp + 16 * s);
+        for (int s = 0; s < 8; ++s) qf[s] = *(const bf16x8 *)(qp + 16 * s);
     }
-    w.m = -INFINITY;
-    w.l = 0.0f;
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) w.acc[dt][r] = 0.0f;
+        for (int r = 0; r < 16; ++r) acc[dt][r] = 0.0f;
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int r = 0; r < 8; ++r) w.pb[t][r] = 0u;
+        for (int r = 0; r < 8; ++r) pb[t][r] = 0u;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { sa[t][r] = 0.0f; sb[t][r] = 0.0f; }
 
     // ---- global -> LDS tile loads.  One instruction moves 1 KiB: lane L's 16
     // bytes land at (wave-uniform LDS base) + 16*L, i.e. row L/16 and physical
@@ -262,11 +224,11 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_kernel(const Params p)
     // V: unit ^ ((row & 3) << 2), so that the 4 rows x 64 bytes a half-wave
     // fetches with the transposing read cover all banks once.
     const size_t kv_row_bytes = (size_t)p.Hkv * HD * 2;
+    const size_t tile_gbytes = (size_t)BN * kv_row_bytes;
     const unsigned char *kg = (const unsigned char *)(p.k + ((size_t)b * p.Skv * p.Hkv + hkv) * HD);
     const unsigned char *vg = (const unsigned char *)(p.v + ((size_t)b * p.Skv * p.Hkv + hkv) * HD);
     const int ld_r = lane >> 4, ld_u = lane & 15;
-    // Byte offset of this lane's 16 bytes from the first row of a tile, for the wave's two chunks.
-    uint32_t koff[2], voff[2];
+    uint32_t koff[2], voff[2];   // byte offset of this lane's 16 bytes from the first row of a tile
     int ld_row[2];
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
@@ -274,13 +236,19 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_kernel(const Params p)
         koff[i] = (uint32_t)(ld_row[i] * kv_row_bytes) + ((ld_u ^ (ld_row[i] & 15)) << 4);
         voff[i] = (uint32_t)(ld_row[i] * kv_row_bytes) + ((ld_u ^ ((ld_row[i] & 3) << 2)) << 4);
     }
+    const uint32_t lds_wave = (uint32_t)(uintptr_t)lds + wave * 2048;
+    auto stage_off = [&](int blk) __attribute__((always_inline)) { return (blk % NSTAGE) * TILE_BYTES; };
+    auto next_stage = [&](int o) __attribute__((always_inline)) {      // stage_off(blk + 1) from stage_off(blk)
+        return o == (NSTAGE - 1) * TILE_BYTES ? 0 : o + TILE_BYTES;
+    };
+    // General form: a request past the last block re-reads the last block into the (dead) stage it
+    // would have used, so the number of loads in flight is the same in every iteration; rows past
+    // the end of a partial tile re-read the last row (they are masked later).
     auto issue_tile = [&](int blk_req, bool is_v) __attribute__((always_inline)) {
-        // A request past the last block re-reads the last block into the (dead) stage it would have
-        // used: the number of loads in flight stays the same in every iteration.
         const int blk = min(blk_req, nblk - 1);
-        const unsigned char *g = (is_v ? vg : kg) + (size_t)blk * BN * kv_row_bytes;
-        const int lbase = (is_v ? V_BASE : 0) + (blk_req % NSTAGE) * TILE_BYTES + wave * 2048;
-        const bool partial = (blk + 1) * BN > p.Skv;          // rows past the end: re-read the last row
+        const unsigned char *g = (is_v ? vg : kg) + (size_t)blk * tile_gbytes;
+        const uint32_t lbase = lds_wave + (is_v ? V_BASE : 0) + stage_off(blk_req);
+        const bool partial = (blk + 1) * BN > p.Skv;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             uint32_t o = is_v ? voff[i] : koff[i];
@@ -288,31 +256,9 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_kernel(const Params p)
                 const int rl = min(ld_row[i], p.Skv - 1 - blk * BN);
                 o = o - (uint32_t)(ld_row[i] * kv_row_bytes) + (uint32_t)(rl * kv_row_bytes);
             }
-            lds_dma16(g, o, (uint32_t)(uintptr_t)(lds + lbase + i * 1024));
+            lds_dma16(g, o, lbase + i * 1024);
         }
     };
-    // Fast form for full, in-range tiles: running tile pointers and LDS stage offsets, no clamping.
-    const size_t tile_gbytes = (size_t)BN * kv_row_bytes;
-    auto issue_loads_fast = [&](const unsigned char *kp, const unsigned char *vp, int kstage, int vstage)
-        __attribute__((always_inline)) {
-#ifdef ABL_NO_DMA
-        return;
-#endif
-        const uint32_t lb = (uint32_t)(uintptr_t)lds + wave * 2048;
-        lds_dma16(kp, koff[0], lb + kstage);
-        lds_dma16(kp, koff[1], lb + kstage + 1024);
-        lds_dma16(vp, voff[0], lb + V_BASE + vstage);
-        lds_dma16(vp, voff[1], lb + V_BASE + vstage + 1024);
-    };
-    // The four loads of one iteration: K(kblk) and V(vblk), this wave's eighth of each tile.
-    auto issue_loads = [&](int kblk, int vblk) __attribute__((always_inline)) {
-#ifdef ABL_NO_DMA
-        return;
-#endif
-        issue_tile(kblk, false);
-        issue_tile(vblk, true);
-    };
-
     // ---- per-lane LDS read addresses
     int kaddr[8];   // K operand: row l32 (+32 per tile), logical unit 2*st + hh
 #pragma unroll
@@ -331,49 +277,36 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_kernel(const Params p)
         }
     }
 
-    // ---- the pieces of one iteration
-    auto stage_off = [&](int blk) __attribute__((always_inline)) { return (blk % NSTAGE) * TILE_BYTES; };
-    auto next_stage = [&](int off) __attribute__((always_inline)) {      // stage_off(blk + 1) from stage_off(blk)
-        return off == (NSTAGE - 1) * TILE_BYTES ? 0 : off + TILE_BYTES;
-    };
-    // S^T(blk) = K(blk) Q^T alone (first block only)
-    auto qk = [&](int blk) __attribute__((always_inline)) {
-        const int kb = (blk % NSTAGE) * TILE_BYTES;
+    // ---- building blocks
+    // S^T = K(stage kb) Q^T alone (prologue).
+    auto qk_only = [&](f32x16 (&s)[2], int kb) __attribute__((always_inline)) {
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) w.s[t][r] = 0.0f;
+            for (int r = 0; r < 16; ++r) s[t][r] = 0.0f;
 #pragma unroll
         for (int st = 0; st < 8; ++st)
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
                 bf16x8 a = *(const LDS_AS bf16x8 *)(lds + kb + t * 32 * ROW_BYTES + kaddr[st]);
-                w.s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, w.qf[st], w.s[t], 0, 0, 0);
+                s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[st], s[t], 0, 0, 0);
             }
     };
-    // The matrix half: O^T += V(vblk)^T P^T (16 MFMAs), then S^T = K(kblk) Q^T (16 MFMAs).
-    // Written as one software-pipelined sequence: the LDS reads of MFMA i+PREFETCH are issued
-    // before MFMA i, so that LDS latency hides behind the matrix pipe.
-    // vb / kb: byte offset of the LDS stage that holds the V / K block (stage_off(block)).
-    auto mat_half = [&](int vb, int kb) __attribute__((always_inline)) {
-#ifdef ABL_NO_MAT
-        return;
-#endif
+    // The 32 MFMAs of one iteration as one software-pipelined sequence: even slots O^T += V^T P^T
+    // (V stage vb, P from pb), odd slots snxt = K Q^T (K stage kb), so that two MFMAs accumulating into
+    // the same registers are four slots apart; the LDS reads of slot i+MAT_PREFETCH are issued before
+    // the MFMA of slot i.  `between(slot)` is called after each MFMA and carries the caller's vector
+    // work for that slot (it must not touch pb entries the remaining PV MFMAs still read).
+    auto mfma_block = [&](f32x16 (&snxt)[2], int vb, int kb, auto between) __attribute__((always_inline)) {
         constexpr int PREFETCH = MAT_PREFETCH;
         bf16x8 frag[32];
-        // stage offsets folded into the per-lane bases once, so every read below is base + immediate
-        int va[4], ka[8];
+        int va[4], ka[8];      // stage offsets folded into the per-lane bases: every read is base + immediate
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt) va[dt] = vaddr[dt] + vb;
 #pragma unroll
         for (int st = 0; st < 8; ++st) ka[st] = kaddr[st] + kb;
-        // Slot i of the sequence: even slots are PV MFMA i/2, odd slots QK MFMA i/2, so that two MFMAs
-        // that accumulate into the same registers are at least four slots apart.
         auto fetch = [&](int slot) __attribute__((always_inline)) -> bf16x8 {
             const int i = slot >> 1;
-#ifdef ABL_NO_LDSREAD
-            return w.qf[i & 7];
-#endif
             if ((slot & 1) == 0) {            // V^T operand of PV MFMA i: key group i/4, d tile i%4
                 const int ro = (i >> 2) * 16 * ROW_BYTES;
                 s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4 *)(lds + va[i & 3] + ro));
@@ -387,85 +320,70 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_kernel(const Params p)
         };
 #pragma unroll
         for (int i = 0; i < PREFETCH; ++i) frag[i] = fetch(i);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int slot = 0; slot < 32; ++slot) {
             if (slot + PREFETCH < 32) frag[slot + PREFETCH] = fetch(slot + PREFETCH);
-#ifdef ABL_MAT_MARKS
-            if (slot == 8 || slot == 16 || slot == 24) TRACE_POINT();
-#endif
             const int i = slot >> 1;
             if ((slot & 1) == 0) {
                 const int g = i >> 2;         // key group: tile g/2, half g%2
-                u32x4 pw = {w.pb[g >> 1][4 * (g & 1)], w.pb[g >> 1][4 * (g & 1) + 1],
-                            w.pb[g >> 1][4 * (g & 1) + 2], w.pb[g >> 1][4 * (g & 1) + 3]};
-                w.acc[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                    frag[slot], __builtin_bit_cast(bf16x8, pw), w.acc[i & 3], 0, 0, 0);
+                u32x4 pw = {pb[g >> 1][4 * (g & 1)], pb[g >> 1][4 * (g & 1) + 1],
+                            pb[g >> 1][4 * (g & 1) + 2], pb[g >> 1][4 * (g & 1) + 3]};
+                acc[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    frag[slot], __builtin_bit_cast(bf16x8, pw), acc[i & 3], 0, 0, 0);
             } else {
                 const int st = i >> 1, t = i & 1;
                 if (st == 0) {
                     f32x16 z;
 #pragma unroll
                     for (int r = 0; r < 16; ++r) z[r] = 0.0f;
-                    w.s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[slot], w.qf[st], z, 0, 0, 0);
+                    snxt[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[slot], qf[st], z, 0, 0, 0);
                 } else {
-                    w.s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[slot], w.qf[st], w.s[t], 0, 0, 0);
+                    snxt[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[slot], qf[st], snxt[t], 0, 0, 0);
                 }
             }
+            between(slot);
+            __builtin_amdgcn_sched_barrier(0);     // keep the slot order exactly as written
         }
-        schedule_matrix_half();
     };
     auto rescale = [&](float mn, float alpha) __attribute__((always_inline)) {
-        w.m = mn;
-        w.l *= alpha;
+        m = mn;
+        l *= alpha;
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) w.acc[dt][r] *= alpha;
+            for (int r = 0; r < 16; ++r) acc[dt][r] *= alpha;
     };
-    // P^T = exp2(S^T * c - m) of an unmasked block into the PV operand registers; returns this lane's
-    // partial row sum (its 16 of every 32 keys), taken from the unrounded FP32 probabilities.
-    auto probabilities = [&]() __attribute__((always_inline)) -> float {
+    // P^T = exp2(S^T * c - m) of an unmasked block into pb; returns this lane's partial row sum,
+    // taken from the unrounded FP32 probabilities.
+    auto probabilities = [&](f32x16 (&s)[2]) __attribute__((always_inline)) -> float {
         float ls0 = 0.0f, ls1 = 0.0f;
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
             for (int r = 0; r < 16; r += 2) {
-                const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(w.s[t][r], p.c, -w.m));
-                const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(w.s[t][r + 1], p.c, -w.m));
+                const float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[t][r], p.c, -m));
+                const float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[t][r + 1], p.c, -m));
                 ls0 += e0;
                 ls1 += e1;
-                w.pb[t][r >> 1] = pack_bf16(e0, e1);
+                pb[t][r >> 1] = pack_bf16(e0, e1);
             }
         return ls0 + ls1;
     };
-    // Raise the running maximum to cover the block in w.s and rescale the accumulator and the row sum.
-    auto raise_reference = [&]() __attribute__((always_inline)) {
-        float mx = max3(w.s[0][0], w.s[0][1], w.s[0][2]);
+    // Raise the running maximum to cover the unmasked block in s; rescale the accumulator and row sum.
+    auto raise_reference = [&](f32x16 (&s)[2]) __attribute__((always_inline)) {
+        float mx = max3(s[0][0], s[0][1], s[0][2]);
 #pragma unroll
-        for (int i = 3; i < 31; i += 2) mx = max3(mx, w.s[i >> 4][i & 15], w.s[(i + 1) >> 4][(i + 1) & 15]);
-        mx = max3(mx, w.s[1][15], w.s[1][15]);
+        for (int i = 3; i < 31; i += 2) mx = max3(mx, s[i >> 4][i & 15], s[(i + 1) >> 4][(i + 1) & 15]);
+        mx = max3(mx, s[1][15], s[1][15]);
         mx = lane32_max(mx) * p.c;
-        const float mn = fmaxf(w.m, mx);
-        rescale(mn, __builtin_amdgcn_exp2f(w.m - mn));
+        const float mn = fmaxf(m, mx);
+        rescale(mn, __builtin_amdgcn_exp2f(m - mn));
     };
-    // Softmax of a block without masked keys.  Softmax is the same against any reference point, so
-    // the probabilities are first formed against the running maximum as it stands, WITHOUT looking
-    // for the block's maximum.  Only if some lane's partial row sum comes out above P_SUM_LIMIT (or
-    // is not a number) did the scores outgrow the reference; then the whole wavefront raises the
-    // reference, rescales, and forms the probabilities again.  The branch is wave-uniform and rare:
-    // with scores of bounded spread the reference settles after the first blocks.
-    auto softmax_fast = [&]() __attribute__((always_inline)) {
-#ifdef ABL_NO_VEC
-        return;
-#endif
-        float ls = probabilities();
-        if (__builtin_amdgcn_ballot_w64(!(ls <= P_SUM_LIMIT)) != 0) {
-            raise_reference();
-            ls = probabilities();
-        }
-        w.l += ls;
-    };
-    auto softmax_masked = [&](int blk) __attribute__((always_inline)) {   // diagonal or tail block: key index per register, limit per lane
+    // Softmax of a block that may hold masked keys (diagonal block, tail block, or a block that lies
+    // wholly past this wavefront's rows): key index per register, limit per lane.  Masked keys get
+    // P = 0 exactly, whatever the score registers hold.
+    auto softmax_masked = [&](f32x16 (&s)[2], int blk) __attribute__((always_inline)) {
         int lim = p.Skv - 1;
         if (CAUSAL) lim = min(lim, q0 + l32 + off);
         const int kidx = blk * BN + 4 * hh;
@@ -475,137 +393,154 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_kernel(const Params p)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int key = kidx + 32 * t + 8 * (r >> 2) + (r & 3);
-                mx = fmaxf(mx, key <= lim ? w.s[t][r] : -INFINITY);
+                mx = fmaxf(mx, key <= lim ? s[t][r] : -INFINITY);
             }
         mx = lane32_max(mx);
         mx = (mx == -INFINITY) ? -INFINITY : mx * p.c;
-        if (__builtin_amdgcn_ballot_w64(mx > w.m + RESCALE_SLACK) != 0) {
-            const float mn = fmaxf(w.m, mx);
-            rescale(mn, (mn == -INFINITY) ? 1.0f : __builtin_amdgcn_exp2f(w.m - mn));
+        if (__builtin_amdgcn_ballot_w64(mx > m) != 0) {
+            const float mn = fmaxf(m, mx);
+            rescale(mn, (mn == -INFINITY) ? 1.0f : __builtin_amdgcn_exp2f(m - mn));
         }
-        const float mu = (w.m == -INFINITY) ? 0.0f : w.m;
+        const float mu = (m == -INFINITY) ? 0.0f : m;
         float ls = 0.0f;
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
             for (int r = 0; r < 16; r += 2) {
                 const int key = kidx + 32 * t + 8 * (r >> 2) + (r & 3);
-                float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(w.s[t][r], p.c, -mu));
-                float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(w.s[t][r + 1], p.c, -mu));
+                float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[t][r], p.c, -mu));
+                float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[t][r + 1], p.c, -mu));
                 e0 = (key <= lim) ? e0 : 0.0f;
                 e1 = (key + 1 <= lim) ? e1 : 0.0f;
                 ls += e0 + e1;
-                w.pb[t][r >> 1] = pack_bf16(e0, e1);
+                pb[t][r >> 1] = pack_bf16(e0, e1);
             }
-        w.l += ls;
+        l += ls;
     };
-    TRACE_ALWAYS();
-    if (nblk > 0) {
-        issue_tile(0, false);
-        issue_loads(1, 0);
-        __builtin_amdgcn_s_waitcnt(WAIT_VMCNT4);          // K(0) has landed
-        PHASE_BARRIER();
 
-        // Wavefronts 0-3 (one per SIMD) run "matrix half, vector half"; wavefronts 4-7 run the same
-        // sequence half an iteration later, so the matrix pipe and the vector ALU of a SIMD are busy
-        // at the same time.  Every half ends with a workgroup barrier.
-        //
-        // K/V tiles live in NSTAGE = 3 LDS stages.  The vector half of iteration j ends by requesting
-        // K(j+3) and V(j+2) (into the stages of K(j) and V(j-1), whose last readers finished at least
-        // one barrier earlier) and then waits until only those four loads are still in flight, i.e.
-        // until K(j+2) and V(j+1) have landed, one barrier before their first reader.  Issuing the
-        // loads from the vector half keeps the address unit's queueing delay off the matrix half.
-        //
+    // Fast iteration j: MFMAs of PV(j) and S(j+2) interleaved with the softmax of S(j+1) = scur.
+    // Softmax is the same against any reference point, so the probabilities are formed against the
+    // running maximum as it stands, WITHOUT looking for the block's maximum first.  Only if some lane's
+    // partial row sum comes out above P_SUM_LIMIT (or is not a number) did the scores outgrow the
+    // reference; then the whole wavefront raises the reference, rescales, and forms the probabilities
+    // again.  That branch is wave-uniform and rare: with scores of bounded spread the reference
+    // settles after the first blocks.
+    // The iteration's four tile requests (K(j+4) from kp into stage kreq, V(j+2) from vp into stage vreq)
+    // are spread over the block, one every eight slots, so that the wavefronts' requests do not queue up
+    // behind each other in the address unit.
+    auto fast_iteration = [&](f32x16 (&scur)[2], f32x16 (&snxt)[2], int vb, int kb,
+                              const unsigned char *kp, const unsigned char *vp, int kreq, int vreq)
+        __attribute__((always_inline)) {
+        float ev[32];
+        uint32_t pn[16];
+        float ls0 = 0.0f, ls1 = 0.0f;
+        mfma_block(snxt, vb, kb, [&](int slot) __attribute__((always_inline)) {
+            // element `slot` of the 32 scores of this lane: exp now, row-sum add one slot later
+#ifdef ABL_NO_EXP
+            ev[slot] = __builtin_fmaf(scur[slot >> 4][slot & 15], p.c, -m);
+#else
+            ev[slot] = __builtin_amdgcn_exp2f(__builtin_fmaf(scur[slot >> 4][slot & 15], p.c, -m));
+#endif
+            if (slot >= 1) {
+                if ((slot - 1) & 1) { ls1 += ev[slot - 1]; PIN(ls1); } else { ls0 += ev[slot - 1]; PIN(ls0); }
+            }
+            // BF16 pair k once the PV MFMAs that read the old pb entry k have been issued
+            // (entries 4g..4g+3 are read by the even slots 8g..8g+6): pair k goes at slot 2k+9
+            if (slot >= 9 && (slot & 1)) {
+                const int k = (slot - 9) >> 1;
+                pn[k] = pack_bf16(ev[2 * k], ev[2 * k + 1]);
+                PIN(pn[k]);
+            }
+            if (slot == 4) lds_dma16(kp, koff[0], lds_wave + kreq);
+            if (slot == 12) lds_dma16(kp, koff[1], lds_wave + kreq + 1024);
+            if (slot == 20) lds_dma16(vp, voff[0], lds_wave + V_BASE + vreq);
+            if (slot == 28) lds_dma16(vp, voff[1], lds_wave + V_BASE + vreq + 1024);
+        });
+        ls1 += ev[31];
+#pragma unroll
+        for (int k = 12; k < 16; ++k) pn[k] = pack_bf16(ev[2 * k], ev[2 * k + 1]);
+#pragma unroll
+        for (int k = 0; k < 16; ++k) pb[k >> 3][k & 7] = pn[k];
+        float ls = ls0 + ls1;
+        if (__builtin_amdgcn_ballot_w64(!(ls <= P_SUM_LIMIT)) != 0) {
+            raise_reference(scur);
+            ls = probabilities(scur);
+        }
+        l += ls;
+    };
+    // General iteration j: the same MFMAs, then the masked softmax of block j+1.
+    auto general_iteration = [&](f32x16 (&scur)[2], f32x16 (&snxt)[2], int vb, int kb, int blk_next)
+        __attribute__((always_inline)) {
+        mfma_block(snxt, vb, kb, [&](int) __attribute__((always_inline)) {});
+        softmax_masked(scur, blk_next);
+    };
+
+    TRACE_MARK();
+    if (nblk > 0) {
+        // Iteration j reads K(j+2) and V(j) and requests K(j+4) and V(j+2) into the stages of K(j+1)
+        // and V(j-1), whose last readers finished before the previous barrier.  It ends by waiting until
+        // only those four loads are still in flight, i.e. until K(j+3) and V(j+1) have landed, then the
+        // barrier publishes them.
+        issue_tile(0, false);
+        issue_tile(1, false);
+        issue_tile(2, false);
+        issue_tile(0, true);
+        __builtin_amdgcn_s_waitcnt(WAIT_VMCNT4);          // K(0), K(1) landed
+        wg_barrier();
+        qk_only(sa, stage_off(0));
+        qk_only(sb, stage_off(1));
+        // P(0): through the masked path, which also handles an empty first block and sets the reference
+        softmax_masked(sa, 0);
+        __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);          // K(2), V(0) landed
+        wg_barrier();                                     // and every wavefront is done with K(0), K(1)
+        issue_tile(3, false);                             // the requests of "iteration -1"
+        issue_tile(1, true);
+
         // Blocks >= n_unm go through the masked softmax, which yields P = 0 where a key is not valid:
-        // blocks that are masked out entirely for this wavefront (and the block past the end that the
-        // last matrix half multiplies from a stale stage) then contribute nothing, with no branch
-        // around the MFMA sequences.
-        if (wave < 4) {
-            qk(0);
-            softmax_masked(0);
-            issue_loads(2, 1);
+        // blocks masked out entirely for this wavefront, and the blocks past the end that the last
+        // iterations multiply from stale stages, then contribute nothing, with no branch around the
+        // MFMA sequences.  Iteration j: scur = S(j+1) (sb for even j), snxt receives S(j+2).
+        int j = 0;
+        int vst = stage_off(0), kst = stage_off(2);               // stages of V(j), K(j+2)
+        const unsigned char *kp = kg + 4 * tile_gbytes, *vp = vg + 2 * tile_gbytes;
+        int kreq = stage_off(4), vreq = stage_off(2);             // stages for K(j+4), V(j+2)
+        const int fast_end = min(n_unm - 1, nload - 4);           // iterations j < fast_end: S(j+1) unmasked, K(j+4) a full tile
+#pragma nounroll
+        for (; j + 1 < fast_end; j += 2) {
+            fast_iteration(sb, sa, vst, kst, kp, vp, kreq, vreq);
+            kp += tile_gbytes; vp += tile_gbytes;
+            kreq = next_stage(kreq); vreq = next_stage(vreq);
+            vst = next_stage(vst); kst = next_stage(kst);
             __builtin_amdgcn_s_waitcnt(WAIT_VMCNT4);
-            PHASE_BARRIER();
-            int j = 0;
-            int vst = stage_off(0), kst = stage_off(1);       // stages of V(j) and K(j+1)
-            // running request state of the fast loop: K(j+3) goes where K(j) was, V(j+2) where V(j-1) was
-            const unsigned char *kp = kg + 3 * tile_gbytes, *vp = vg + 2 * tile_gbytes;
-            int kreq = stage_off(3), vreq = stage_off(2);
-#pragma nounroll
-            for (; j + 1 < n_unm && j + 3 < nload; ++j) {
-                MAT_PRIO(1);
-                mat_half(vst, kst);
-                MAT_PRIO(0);
-                vst = next_stage(vst);
-                kst = next_stage(kst);
-                MID_BARRIER();
-                softmax_fast();
-                issue_loads_fast(kp, vp, kreq, vreq);
-                kp += tile_gbytes;
-                vp += tile_gbytes;
-                kreq = next_stage(kreq);
-                vreq = next_stage(vreq);
-                __builtin_amdgcn_s_waitcnt(WAIT_VMCNT4);
-                PHASE_BARRIER();
-            }
-#pragma nounroll
-            for (; j < nblk; ++j) {
-                MAT_PRIO(1);
-                mat_half(vst, kst);
-                MAT_PRIO(0);
-                vst = next_stage(vst);
-                kst = next_stage(kst);
-                MID_BARRIER();
-                softmax_masked(j + 1);
-                issue_loads(j + 3, j + 2);
-                __builtin_amdgcn_s_waitcnt(WAIT_VMCNT4);
-                PHASE_BARRIER();
-            }
-        } else {
-            issue_loads(2, 1);
-            qk(0);
+            wg_barrier();
+            fast_iteration(sa, sb, vst, kst, kp, vp, kreq, vreq);
+            kp += tile_gbytes; vp += tile_gbytes;
+            kreq = next_stage(kreq); vreq = next_stage(vreq);
+            vst = next_stage(vst); kst = next_stage(kst);
             __builtin_amdgcn_s_waitcnt(WAIT_VMCNT4);
-            PHASE_BARRIER();
-            int j = 0;
-            int vst = stage_off(0), kst = stage_off(1);       // stages of V(j) and K(j+1)
-            const unsigned char *kp = kg + 3 * tile_gbytes, *vp = vg + 2 * tile_gbytes;
-            int kreq = stage_off(3), vreq = stage_off(2);
+            wg_barrier();
+        }
 #pragma nounroll
-            for (; j < n_unm && j + 3 < nload; ++j) {
-                softmax_fast();
-                issue_loads_fast(kp, vp, kreq, vreq);
-                kp += tile_gbytes;
-                vp += tile_gbytes;
-                kreq = next_stage(kreq);
-                vreq = next_stage(vreq);
-                MID_BARRIER();
-                MAT_PRIO(1);
-                mat_half(vst, kst);
-                MAT_PRIO(0);
-                vst = next_stage(vst);
-                kst = next_stage(kst);
+        for (; j < nblk; j += 2) {
+            general_iteration(sb, sa, stage_off(j), stage_off(j + 2), j + 1);
+            issue_tile(j + 4, false);
+            issue_tile(j + 2, true);
+            __builtin_amdgcn_s_waitcnt(WAIT_VMCNT4);
+            wg_barrier();
+            if (j + 1 < nblk) {
+                general_iteration(sa, sb, stage_off(j + 1), stage_off(j + 3), j + 2);
+                issue_tile(j + 5, false);
+                issue_tile(j + 3, true);
                 __builtin_amdgcn_s_waitcnt(WAIT_VMCNT4);
-                PHASE_BARRIER();
-            }
-#pragma nounroll
-            for (; j < nblk; ++j) {
-                softmax_masked(j);
-                issue_loads(j + 3, j + 2);
-                MID_BARRIER();
-                MAT_PRIO(1);
-                mat_half(vst, kst);
-                MAT_PRIO(0);
-                vst = next_stage(vst);
-                kst = next_stage(kst);
-                __builtin_amdgcn_s_waitcnt(WAIT_VMCNT4);
-                PHASE_BARRIER();
+                wg_barrier();
             }
         }
+        __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);          // nothing may still be writing LDS at exit
     }
+    TRACE_MARK();
 
-    TRACE_ALWAYS();
     // ---- epilogue: O = acc / l (BF16), LSE = ln2 * (m + log2 l)
-    const float lt = lane32_sum(w.l);
+    const float lt = lane32_sum(l);
     const float inv = lt > 0.0f ? 1.0f / lt : 0.0f;
     const int qrow = q0 + l32;
     if (qrow < p.Sq) {
@@ -614,12 +549,12 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_kernel(const Params p)
         for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
             for (int rg = 0; rg < 4; ++rg) {
-                u32x2 ww = {pack_bf16(w.acc[dt][4 * rg] * inv, w.acc[dt][4 * rg + 1] * inv),
-                            pack_bf16(w.acc[dt][4 * rg + 2] * inv, w.acc[dt][4 * rg + 3] * inv)};
+                u32x2 ww = {pack_bf16(acc[dt][4 * rg] * inv, acc[dt][4 * rg + 1] * inv),
+                            pack_bf16(acc[dt][4 * rg + 2] * inv, acc[dt][4 * rg + 3] * inv)};
                 *(u32x2 *)(op + 32 * dt + 8 * rg) = ww;
             }
         if (hh == 0) {
-            const float lse = lt > 0.0f ? (w.m + __builtin_amdgcn_logf(lt)) * 0.6931471805599453f : -INFINITY;
+            const float lse = lt > 0.0f ? (m + __builtin_amdgcn_logf(lt)) * 0.6931471805599453f : -INFINITY;
             p.lse[((size_t)b * p.Hq + head) * p.Sq + qrow] = lse;
         }
     }
@@ -651,7 +586,7 @@ int attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
     p.ntile = (Sq + p.tile_pos - 1) / p.tile_pos;
     p.chunks = p.G / p.pack;
     // Key/query indices and the work-item count are 32-bit in the kernel.
-    if ((int64_t)Sq + Skv + WG_ROWS + BN >= INT32_MAX) return ATTN_E_UNSUPPORTED;
+    if ((int64_t)Sq + Skv + WG_ROWS + 8 * BN >= INT32_MAX) return ATTN_E_UNSUPPORTED;
     const int64_t total = (int64_t)B * Hkv * p.chunks * p.ntile;
     if (total + 8 >= INT32_MAX) return ATTN_E_UNSUPPORTED;
     p.total = (int)total;
