@@ -28,25 +28,52 @@ PEAK_BF16_TFLOPS = 2516.6      # MI355X dense BF16 MFMA: 256 CU x 4 SIMD x 1024 
 METRIC = "attention fwd TFLOPS (BF16, D=128) and % of MI355X dense BF16 MFMA peak"
 
 
-def measured_traffic(name):
-    """HBM bytes per launch recorded from rocprofv3 counter runs (profiles/hbm_traffic.json), or None."""
-    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+def mfma_probe():
+    """What a bare MFMA loop sustains on this board for all-zero and for N(0,1) BF16 operands (context for `frac`)."""
+    dev = torch.device("cuda:0")
+    stream = torch.cuda.current_stream()
+    sink = torch.zeros(1, dtype=torch.float32, device=dev)
+    g = torch.Generator().manual_seed(7)
+    out = {}
+    iters = 2000
+    flops = A.MFMA_PROBE_BLOCKS * 4 * iters * 32 * 32768.0
+    for name, ops in (("zeros", torch.zeros(12, 64, 8)), ("normal", torch.randn(12, 64, 8, generator=g))):
+        ops = ops.to(torch.bfloat16).to(dev)
+        for _ in range(2):
+            rc = A.attn_mfma_probe(ops, sink, iters, stream.cuda_stream)
+            if rc != 0:
+                raise A.AttnError(rc)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(5):
+            A.attn_mfma_probe(ops, sink, iters, stream.cuda_stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        out[name] = flops * 5 / (e0.elapsed_time(e1) * 1e-3) * 1e-12
+    return {"unit": "TFLOP/s", "what": "bare v_mfma_f32_32x32x16_bf16 loop, register operands, 4 waves/CU",
+            "zeros": out["zeros"], "normal_0_1": out["normal"]}
+
+
+def traffic_from_profiles(name):
+    """HBM bytes per launch from the committed counter summary (profiles/attn_fwd_kernel_hbm_traffic.md), or None."""
+    import re
+    path = os.path.join(ROOT, "profiles", "attn_fwd_kernel_hbm_traffic.md")
     if not os.path.exists(path):
         return None
-    with open(path) as f:
-        return json.load(f).get(name, {}).get("bytes_per_launch")
+    m = re.search(r"traffic_bytes_per_launch\[%s\]\s*=\s*(\d+)" % re.escape(name), open(path).read())
+    return int(m.group(1)) if m else None
 
 
 def cpu_baseline(w, q, k, v, o_gpu, lse_gpu, budget_s=12.0):
     """Time the FP64 oracle (as it stands) on a bounded row sample and check the GPU output on it."""
     import oracle
-    rows_all = W.sample_rows(w, 16384)
+    rows_all = W.sample_rows(w, 393216)
     qd, kd, vd = q.double().numpy(), k.double().numpy(), v.double().numpy()
     pilot = rows_all[:: max(1, len(rows_all) // 256)][:256]
     t0 = time.perf_counter()
     oracle.attn_ref_rows(qd, kd, vd, pilot, w.causal, w.scale)
     dt = max(time.perf_counter() - t0, 1e-4)
-    n = int(min(len(rows_all), max(256, budget_s / dt * len(pilot))))
+    n = int(min(len(rows_all), max(256, budget_s / dt * len(pilot))))   # about budget_s seconds of oracle work
     rows = rows_all[:: max(1, len(rows_all) // n)][:n]
     t0 = time.perf_counter()
     o_ref, lse_ref = oracle.attn_ref_rows(qd, kd, vd, rows, w.causal, w.scale)
@@ -110,7 +137,7 @@ def run_workload(name, steps, warmup, with_cpu, repeats=1):
                    "causal": w.causal, "q_mul": w.q_mul, "v_dist": w.v_dist, "seed": w.seed,
                    "flops_per_step": w.flops},
         "roofline": {"bound": "mfma", "achieved": ktflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": ktflops / PEAK_BF16_TFLOPS, "traffic": measured_traffic(w.name),
+                     "frac": ktflops / PEAK_BF16_TFLOPS, "traffic": traffic_from_profiles(w.name),
                      "kernel": "attn_fwd_kernel", "kernel_ms": kms,
                      "algorithmic_bytes": w.algorithmic_bytes},
     }
@@ -118,6 +145,7 @@ def run_workload(name, steps, warmup, with_cpu, repeats=1):
         out["ms_std"] = float(np.std(dev_ms))
     if with_cpu:
         out["cpu_baseline"], out["parity"] = cpu_baseline(w, q, k, v, o, lse)
+        out["mfma_probe"] = mfma_probe()
     return out
 
 
@@ -129,12 +157,23 @@ def main():
     ap.add_argument("--workload", default=W.HEADLINE, choices=sorted(W.WORKLOADS))
     ap.add_argument("--all", action="store_true", help="every workload, 10 repeats of --steps each")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run a plain 1 GiB device copy instead (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1")
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; there is no CPU path")
     A.load()
+    if args.copy_calibration:
+        n = 1 << 30
+        src = torch.full((n,), 3, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": n, "copy_bytes_written": n, "launches": 3}))
+        return
     if args.all:
         names = [n for n in W.WORKLOADS if n != W.HEADLINE] + [W.HEADLINE]
         for n in names:

@@ -60,6 +60,22 @@ int attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
              int B, int Hq, int Hkv, int Sq, int Skv, int D,
              int causal, float scale, void *stream);
 
+/*
+ * attn_mfma_probe -- measurement aid, not part of the attention path: what the matrix pipe sustains
+ * on this board for given operand data, as context for the TFLOPS figure that section 4.1 of the
+ * paper uses as its metric.  Launches ATTN_MFMA_PROBE_BLOCKS workgroups of 4 wavefronts; every
+ * wavefront issues iters * 32 independent v_mfma_f32_32x32x16_bf16 (32768 FLOP each) on register
+ * operands read once from `operands`, so one launch performs
+ *     ATTN_MFMA_PROBE_BLOCKS * 4 * iters * 32 * 32768 FLOP.
+ *   operands  in   device, BF16 [12, 64, 8], 16-byte aligned (8 A and 4 B operand sets per lane)
+ *   sink      out  device, 1 float (written only in a case that does not occur in practice)
+ *   iters     1 .. 2^20
+ *   stream    a hipStream_t, or NULL
+ * Enqueues only; returns ATTN_OK or a negative code after host-side checks.
+ */
+#define ATTN_MFMA_PROBE_BLOCKS 256
+int attn_mfma_probe(const void *operands, float *sink, int iters, void *stream);
+
 /* Static text for a return code of this library (never NULL). */
 const char *attn_strerror(int code);
 

@@ -40,6 +40,8 @@ def load():
         vp, ci = ctypes.c_void_p, ctypes.c_int
         lib.attn_fwd.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ctypes.c_float, vp]
         lib.attn_fwd.restype = ci
+        lib.attn_mfma_probe.argtypes = [vp, vp, ci, vp]
+        lib.attn_mfma_probe.restype = ci
         lib.attn_strerror.argtypes = [ci]
         lib.attn_strerror.restype = ctypes.c_char_p
         lib.attn_version.argtypes = []
@@ -65,6 +67,14 @@ def attn_fwd(q, k, v, o, lse, B, Hq, Hkv, Sq, Skv, D, causal, scale, stream=None
     return load().attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse),
                            int(B), int(Hq), int(Hkv), int(Sq), int(Skv), int(D),
                            int(bool(causal)), float(scale), stream)
+
+
+MFMA_PROBE_BLOCKS = 256
+
+
+def attn_mfma_probe(operands, sink, iters, stream=None):
+    """C-ABI call attn_mfma_probe(...): measurement aid, see include/attn.h.  Returns the status code."""
+    return load().attn_mfma_probe(_ptr(operands), _ptr(sink), int(iters), stream)
 
 
 def attn_strerror(code):

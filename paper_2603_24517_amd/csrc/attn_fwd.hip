@@ -560,6 +560,35 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_kernel(const Params p)
     }
 }
 
+// Measurement aid: a loop of independent 32x32x16 BF16 MFMAs on register operands read once from
+// `operands` (12 x 64 lanes x 8 BF16).  No LDS, no vector arithmetic, no memory traffic in the loop:
+// what it sustains is the matrix-pipe rate the board's power management allows for that data.
+__global__ __launch_bounds__(256) void mfma_probe_kernel(const bf16x8 *operands, float *sink, int iters)
+{
+    bf16x8 a[8], b[4];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) a[i] = operands[i * 64 + (threadIdx.x & 63)];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) b[i] = operands[(8 + i) * 64 + (threadIdx.x & 63)];
+    f32x16 c[4];
+#pragma unroll
+    for (int n = 0; n < 4; ++n)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) c[n][r] = 0.0f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int n = 0; n < 4; ++n) c[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[n], c[n], 0, 0, 0);
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int n = 0; n < 4; ++n)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s += c[n][r];
+    if (s == 123.456f) sink[0] = s;     // keeps the loop alive; practically never true
+}
+
 }  // namespace
 
 extern "C" {
@@ -613,6 +642,16 @@ int attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
         hipLaunchKernelGGL(attn_fwd_kernel<true>, grid, block, LDS_BYTES, st, p);
     else
         hipLaunchKernelGGL(attn_fwd_kernel<false>, grid, block, LDS_BYTES, st, p);
+    return hipGetLastError() == hipSuccess ? ATTN_OK : ATTN_E_LAUNCH;
+}
+
+int attn_mfma_probe(const void *operands, float *sink, int iters, void *stream)
+{
+    if (!operands || !sink) return ATTN_E_NULL;
+    if (iters <= 0 || iters > (1 << 20)) return ATTN_E_SHAPE;
+    if ((uintptr_t)operands & 15) return ATTN_E_ALIGN;
+    hipLaunchKernelGGL(mfma_probe_kernel, dim3(ATTN_MFMA_PROBE_BLOCKS), dim3(256), 0, (hipStream_t)stream,
+                       (const bf16x8 *)operands, sink, iters);
     return hipGetLastError() == hipSuccess ? ATTN_OK : ATTN_E_LAUNCH;
 }
 

@@ -65,3 +65,12 @@ def test_no_cpu_fallback():
     x = torch.zeros(1, 8, 2, 128, dtype=torch.bfloat16)
     with pytest.raises(ValueError):
         A.attention(x, x, x)
+
+
+@pytest.mark.parametrize("args,code", [
+    ((None, 4096, 10), A.ATTN_E_NULL), ((4096, None, 10), A.ATTN_E_NULL),
+    ((4096, 8192, 0), A.ATTN_E_SHAPE), ((4096, 8192, 1 << 21), A.ATTN_E_SHAPE),
+    ((4096 + 4, 8192, 10), A.ATTN_E_ALIGN),
+])
+def test_mfma_probe_bad_arguments(args, code):
+    assert A.attn_mfma_probe(*args) == code

@@ -155,3 +155,11 @@ def test_configs_sampled_rows(name):
     rows = W.sample_rows(w, 1536)
     r = U.check_rows(q, k, v, rows, w.causal, w.scale, what=name)
     print(name, r, flush=True)
+
+
+def test_mfma_probe_runs_gpu():
+    ops = torch.randn(12, 64, 8).to(torch.bfloat16).cuda()
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    assert A.attn_mfma_probe(ops, sink, 10, torch.cuda.current_stream().cuda_stream) == 0
+    torch.cuda.synchronize()
+    assert float(sink.item()) == 0.0
