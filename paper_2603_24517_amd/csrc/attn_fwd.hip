@@ -65,7 +65,7 @@ constexpr int LDS_BYTES = 2 * NSTAGE * TILE_BYTES;
 // stay below 2^14 relative to the reference maximum, far inside BF16 / FP32 range.
 constexpr float P_SUM_LIMIT = 16384.0f;
 #ifndef MAT_PREFETCH
-#define MAT_PREFETCH 4               // LDS reads run this many MFMAs ahead of their consumer
+#define MAT_PREFETCH 3               // LDS reads run this many MFMAs ahead of their consumer
 #endif
 constexpr int WAIT_VMCNT0 = 0x0F70;  // s_waitcnt vmcnt(0), other counters untouched
 constexpr int WAIT_VMCNT4 = 0x0F74;  // s_waitcnt vmcnt(4): all but the 4 most recent loads have landed
@@ -171,20 +171,23 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_kernel(const Params p)
     const int q0 = tile * p.tile_pos + (wave / p.pack) * 32;   // first query row of this wave
     const int off = p.Skv - p.Sq;                               // causal: key j valid iff j <= i + off
 
-    // ---- block counts: nblk for the workgroup (one barrier each); of these the
-    // first n_unm need no mask for any row of this wavefront; nload of them are
-    // full tiles.
+    // ---- block counts: nblk for the workgroup (one barrier each); n_w of them hold a key that is
+    // valid for some row of this wavefront, and the first n_unm of those need no mask at all.
     int nblk = (p.Skv + BN - 1) / BN;
     int n_unm = p.Skv / BN;
+    int n_w = nblk;
     if (CAUSAL) {
         const int qlast = min(tile * p.tile_pos + p.tile_pos, p.Sq) - 1;
         const int klast = qlast + off;
         nblk = klast < 0 ? 0 : min(nblk, klast / BN + 1);
+        const int klast_w = q0 + 31 + off;          // last key valid for the last row of the wave
+        n_w = klast_w < 0 ? 0 : min(nblk, klast_w / BN + 1);
         const int kfirst_w = q0 + off + 1;          // number of keys valid for every row of the wave
         n_unm = min(n_unm, kfirst_w <= 0 ? 0 : kfirst_w / BN);
     }
-    n_unm = min(n_unm, nblk);
-    const int nload = min(nblk, p.Skv / BN);
+    n_unm = min(n_unm, n_w);
+    const int nfull = p.Skv / BN;                   // tiles below this index are full
+    const bool all_full = (p.Skv % BN) == 0;
 
 #ifdef ATTN_TRACE
     int trace_n = 0;
@@ -468,11 +471,13 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_kernel(const Params p)
         }
         l += ls;
     };
-    // General iteration j: the same MFMAs, then the masked softmax of block j+1.
-    auto general_iteration = [&](f32x16 (&scur)[2], f32x16 (&snxt)[2], int vb, int kb, int blk_next)
-        __attribute__((always_inline)) {
-        mfma_block(snxt, vb, kb, [&](int) __attribute__((always_inline)) {});
-        softmax_masked(scur, blk_next);
+    // General iteration j: the MFMA block unless block j (and with it every later block) is wholly masked
+    // for this wavefront, then the masked softmax of block j+1 unless that one is wholly masked.
+    auto general_iteration = [&](f32x16 (&scur)[2], f32x16 (&snxt)[2], int j) __attribute__((always_inline)) {
+        if (j < n_w)
+            mfma_block(snxt, stage_off(j), stage_off(j + 2), [&](int) __attribute__((always_inline)) {});
+        __builtin_amdgcn_sched_barrier(0);
+        if (j + 1 < n_w) softmax_masked(scur, j + 1);
     };
 
     TRACE_MARK();
@@ -502,19 +507,21 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_kernel(const Params p)
         // MFMA sequences.  Iteration j: scur = S(j+1) (sb for even j), snxt receives S(j+2).
         int j = 0;
         int vst = stage_off(0), kst = stage_off(2);               // stages of V(j), K(j+2)
-        const unsigned char *kp = kg + 4 * tile_gbytes, *vp = vg + 2 * tile_gbytes;
         int kreq = stage_off(4), vreq = stage_off(2);             // stages for K(j+4), V(j+2)
-        const int fast_end = min(n_unm - 1, nload - 4);           // iterations j < fast_end: S(j+1) unmasked, K(j+4) a full tile
+        // Iterations j < fast_end take the fast path: S(j+1) needs no mask, and the tiles requested are
+        // full ones (a request past the last block re-reads the last block, which is full here).
+        const int fast_end = all_full ? n_unm - 1 : min(n_unm - 1, nfull - 4);
+        auto tile_ptr = [&](const unsigned char *g, int blk) __attribute__((always_inline)) {
+            return g + (size_t)min(blk, nblk - 1) * tile_gbytes;
+        };
 #pragma nounroll
         for (; j + 1 < fast_end; j += 2) {
-            fast_iteration(sb, sa, vst, kst, kp, vp, kreq, vreq);
-            kp += tile_gbytes; vp += tile_gbytes;
+            fast_iteration(sb, sa, vst, kst, tile_ptr(kg, j + 4), tile_ptr(vg, j + 2), kreq, vreq);
             kreq = next_stage(kreq); vreq = next_stage(vreq);
             vst = next_stage(vst); kst = next_stage(kst);
             __builtin_amdgcn_s_waitcnt(WAIT_VMCNT4);
             wg_barrier();
-            fast_iteration(sa, sb, vst, kst, kp, vp, kreq, vreq);
-            kp += tile_gbytes; vp += tile_gbytes;
+            fast_iteration(sa, sb, vst, kst, tile_ptr(kg, j + 5), tile_ptr(vg, j + 3), kreq, vreq);
             kreq = next_stage(kreq); vreq = next_stage(vreq);
             vst = next_stage(vst); kst = next_stage(kst);
             __builtin_amdgcn_s_waitcnt(WAIT_VMCNT4);
@@ -522,13 +529,13 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_kernel(const Params p)
         }
 #pragma nounroll
         for (; j < nblk; j += 2) {
-            general_iteration(sb, sa, stage_off(j), stage_off(j + 2), j + 1);
+            general_iteration(sb, sa, j);
             issue_tile(j + 4, false);
             issue_tile(j + 2, true);
             __builtin_amdgcn_s_waitcnt(WAIT_VMCNT4);
             wg_barrier();
             if (j + 1 < nblk) {
-                general_iteration(sa, sb, stage_off(j + 1), stage_off(j + 3), j + 2);
+                general_iteration(sa, sb, j + 1);
                 issue_tile(j + 5, false);
                 issue_tile(j + 3, true);
                 __builtin_amdgcn_s_waitcnt(WAIT_VMCNT4);
