@@ -98,6 +98,11 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
     bf16x2 p = __builtin_convertvector((f32x2){a, b}, bf16x2);   // v_cvt_pk_bf16_f32, nearest even
     return __builtin_bit_cast(uint32_t, p);
 }
+// acc + lo(p) + hi(p) for a pair of BF16 values (v_dot2c_f32_bf16 against (1, 1)).
+__device__ __forceinline__ float add_bf16_pair(uint32_t p, float acc) {
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, p), ones, acc, false);
+}
 __device__ __forceinline__ float max3(float a, float b, float c) {
     float r;
     asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
@@ -199,7 +204,11 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_kernel(const Params p)
     uint32_t pb[2][8];     // P^T of the block whose PV product comes next, BF16 pairs
     f32x16 acc[4];         // O^T accumulator: four 32-d tiles
     float m = -INFINITY;   // running maximum in log2 units (score * scale * log2 e)
-    float l = 0.0f;        // this lane's share of the running sum (its 16 of every 32 keys)
+    float l = 0.0f;        // this lane's share of the running sum (its 16 of every 32 keys), unrounded FP32
+                           // probabilities: the sum LSE is formed from
+    float lr = 0.0f;       // the same sum over the BF16-rounded probabilities that multiply V: O is
+                           // normalised by this one, so that a rounding error in a dominant weight
+                           // cancels between numerator and denominator
     {
         const int qrow = min(q0 + l32, p.Sq - 1);
         const __bf16 *qp = p.q + ((size_t)((size_t)b * p.Sq + qrow) * p.Hq + head) * HD + 8 * hh;
@@ -352,15 +361,16 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_kernel(const Params p)
     auto rescale = [&](float mn, float alpha) __attribute__((always_inline)) {
         m = mn;
         l *= alpha;
+        lr *= alpha;
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[dt][r] *= alpha;
     };
-    // P^T = exp2(S^T * c - m) of an unmasked block into pb; returns this lane's partial row sum,
-    // taken from the unrounded FP32 probabilities.
-    auto probabilities = [&](f32x16 (&s)[2]) __attribute__((always_inline)) -> float {
-        float ls0 = 0.0f, ls1 = 0.0f;
+    // P^T = exp2(S^T * c - m) of an unmasked block into pb; returns this lane's partial row sums: over
+    // the unrounded FP32 probabilities, and (through lrs) over the BF16-rounded ones.
+    auto probabilities = [&](f32x16 (&s)[2], float &lrs) __attribute__((always_inline)) -> float {
+        float ls0 = 0.0f, ls1 = 0.0f, r0 = 0.0f;
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
@@ -370,7 +380,9 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_kernel(const Params p)
                 ls0 += e0;
                 ls1 += e1;
                 pb[t][r >> 1] = pack_bf16(e0, e1);
+                r0 = add_bf16_pair(pb[t][r >> 1], r0);
             }
+        lrs = r0;
         return ls0 + ls1;
     };
     // Raise the running maximum to cover the unmasked block in s; rescale the accumulator and row sum.
@@ -417,6 +429,7 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_kernel(const Params p)
                 e1 = (key + 1 <= lim) ? e1 : 0.0f;
                 ls += e0 + e1;
                 pb[t][r >> 1] = pack_bf16(e0, e1);
+                lr = add_bf16_pair(pb[t][r >> 1], lr);
             }
         l += ls;
     };
@@ -436,7 +449,7 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_kernel(const Params p)
         __attribute__((always_inline)) {
         float ev[32];
         uint32_t pn[16];
-        float ls0 = 0.0f, ls1 = 0.0f;
+        float ls0 = 0.0f, ls1 = 0.0f, lrn = 0.0f;
         mfma_block(snxt, vb, kb, [&](int slot) __attribute__((always_inline)) {
             // element `slot` of the 32 scores of this lane: exp now, row-sum add one slot later
 #ifdef ABL_NO_EXP
@@ -453,6 +466,7 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_kernel(const Params p)
                 const int k = (slot - 9) >> 1;
                 pn[k] = pack_bf16(ev[2 * k], ev[2 * k + 1]);
                 PIN(pn[k]);
+                lrn = add_bf16_pair(pn[k], lrn);
             }
             if (slot == 4) lds_dma16(kp, koff[0], lds_wave + kreq);
             if (slot == 12) lds_dma16(kp, koff[1], lds_wave + kreq + 1024);
@@ -461,15 +475,19 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_kernel(const Params p)
         });
         ls1 += ev[31];
 #pragma unroll
-        for (int k = 12; k < 16; ++k) pn[k] = pack_bf16(ev[2 * k], ev[2 * k + 1]);
+        for (int k = 12; k < 16; ++k) {
+            pn[k] = pack_bf16(ev[2 * k], ev[2 * k + 1]);
+            lrn = add_bf16_pair(pn[k], lrn);
+        }
 #pragma unroll
         for (int k = 0; k < 16; ++k) pb[k >> 3][k & 7] = pn[k];
         float ls = ls0 + ls1;
         if (__builtin_amdgcn_ballot_w64(!(ls <= P_SUM_LIMIT)) != 0) {
             raise_reference(scur);
-            ls = probabilities(scur);
+            ls = probabilities(scur, lrn);
         }
         l += ls;
+        lr += lrn;
     };
     // General iteration j: the MFMA block unless block j (and with it every later block) is wholly masked
     // for this wavefront, then the masked softmax of block j+1 unless that one is wholly masked.
@@ -546,9 +564,10 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_kernel(const Params p)
     }
     TRACE_MARK();
 
-    // ---- epilogue: O = acc / l (BF16), LSE = ln2 * (m + log2 l)
+    // ---- epilogue: O = acc / lr (BF16), LSE = ln2 * (m + log2 l)
     const float lt = lane32_sum(l);
-    const float inv = lt > 0.0f ? 1.0f / lt : 0.0f;
+    const float lrt = lane32_sum(lr);
+    const float inv = lrt > 0.0f ? 1.0f / lrt : 0.0f;
     const int qrow = q0 + l32;
     if (qrow < p.Sq) {
         __bf16 *op = p.o + ((size_t)((size_t)b * p.Sq + qrow) * p.Hq + head) * HD + 4 * hh;

@@ -66,6 +66,18 @@ WORKLOADS = {w.name: w for w in [
     _w("cfg5b_gqa8_nc_b1_s32768_vu", 1, 64, 8, 32768, False, 1010, v_dist="uniform"),
 ]}
 
+# The rest of the paper's own benchmark grid (section 4.1: MHA 16 heads, causal and non-causal, at the four
+# (batch, sequence) points; section 4.3: 32 query heads with 8 or 4 KV heads): the shapes the list above does
+# not already cover.  Same generators, seeds 2001...
+_SWEEP = [(8, 4096), (4, 8192), (2, 16384), (1, 32768)]
+PAPER_GRID = {w.name: w for w in (
+    [_w(f"grid_mha_nc_b{b}_s{s}", b, 16, 16, s, False, 2001 + i) for i, (b, s) in enumerate(_SWEEP)] +
+    [_w(f"grid_mha_c_b{b}_s{s}", b, 16, 16, s, True, 2011 + i) for i, (b, s) in enumerate(_SWEEP)] +
+    [_w(f"grid_gqa4_{'c' if c else 'nc'}_b{b}_s{s}", b, 32, 8, s, c, 2021 + 4 * c + i)
+     for c in (False, True) for i, (b, s) in enumerate(_SWEEP)] +
+    [_w(f"grid_gqa8_{'c' if c else 'nc'}_b{b}_s{s}", b, 32, 4, s, c, 2031 + 4 * c + i)
+     for c in (False, True) for i, (b, s) in enumerate(_SWEEP)])}
+
 SMALL = "cfg1_mha_nc_b1_h4_s512"
 HEADLINE = "cfg2_mha_nc_b8_h16_s4096"
 

@@ -163,3 +163,41 @@ def test_mfma_probe_runs_gpu():
     assert A.attn_mfma_probe(ops, sink, 10, torch.cuda.current_stream().cuda_stream) == 0
     torch.cuda.synchronize()
     assert float(sink.item()) == 0.0
+
+
+def test_random_shapes_gpu():
+    """Seeded sweep of irregular shapes: head packing, ragged tiles on both axes, Sq != Skv, odd batch."""
+    rng = np.random.default_rng(20260324)
+    for n in range(28):
+        hkv = int(rng.choice([1, 2, 3, 5]))
+        g = int(rng.choice([1, 2, 3, 4, 6, 8, 16]))
+        B = int(rng.integers(1, 4))
+        Sq = int(rng.integers(1, 700))
+        Skv = int(rng.integers(1, 900))
+        causal = bool(rng.integers(0, 2))
+        q_mul = float(rng.choice([1.0, 1.0, 4.0]))
+        print(f"case {n}: B={B} Hq={hkv * g} Hkv={hkv} Sq={Sq} Skv={Skv} causal={causal} q_mul={q_mul}", flush=True)
+        q, k, v = U.rand_qkv(B, hkv * g, hkv, Sq, Skv, seed=1000 + n, q_mul=q_mul)
+        U.check_full(q, k, v, causal, SCALE, what=f"random case {n}")
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_long_ragged_sequence(causal):
+    q, k, v = U.rand_qkv(1, 4, 2, 1000, 5037, seed=31)
+    U.check_full(q, k, v, causal, SCALE, what="long ragged")
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_scores_jump_mid_sequence(causal):
+    """Small scores for the first 1024 keys, then keys 40x larger: the running reference must be raised
+    in the middle of the unmasked fast path (probabilities overflow the fast path's limit there)."""
+    q, k, v = U.rand_qkv(1, 2, 2, 2048, 2048, seed=32)
+    k = k.float()
+    k[:, 1024:] *= 40.0
+    U.check_full(q, k.to(torch.bfloat16), v, causal, SCALE, what="score jump")
+
+
+def test_huge_scores_overflow_exp():
+    """Scores of several hundred: exp2 of the first guess overflows to inf, the exact path must take over."""
+    q, k, v = U.rand_qkv(1, 2, 2, 640, 1024, seed=33, q_mul=64.0)
+    U.check_full(q, k, v, False, 1.0, what="huge scores")
