@@ -53,12 +53,21 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int HD = 128;              // head dimension
 constexpr int BN = 64;               // keys per K/V block
-constexpr int NWAVES = 8;            // wavefronts per workgroup
+#ifndef ATTN_NWAVES
+#define ATTN_NWAVES 8
+#endif
+#ifndef ATTN_NSTAGE
+#define ATTN_NSTAGE 3
+#endif
+constexpr int NWAVES = ATTN_NWAVES;  // wavefronts per workgroup: 8 (one workgroup per CU, three LDS stages); 4 with
+                                     // two stages (two workgroups per CU) measures the same and doubles L2 traffic
 constexpr int NTHREADS = NWAVES * 64;
 constexpr int WG_ROWS = NWAVES * 32; // query rows per workgroup
 constexpr int ROW_BYTES = HD * 2;    // one (token, head) row of BF16
 constexpr int TILE_BYTES = BN * ROW_BYTES;
-constexpr int NSTAGE = 3;                   // K/V tiles in flight: requested two iterations ahead
+constexpr int NSTAGE = ATTN_NSTAGE;         // LDS stages per operand
+constexpr int REQ_AHEAD = NSTAGE - 1;       // tiles are requested this many iterations before use
+constexpr int LPT = 16 / NWAVES;            // 1 KiB load instructions per tile and wavefront
 constexpr int V_BASE = NSTAGE * TILE_BYTES; // K stages first, V stages after them
 constexpr int LDS_BYTES = 2 * NSTAGE * TILE_BYTES;
 // Largest partial row sum (16 probabilities of one lane) the fast softmax path accepts: probabilities
@@ -67,9 +76,10 @@ constexpr float P_SUM_LIMIT = 16384.0f;
 #ifndef MAT_PREFETCH
 #define MAT_PREFETCH 3               // LDS reads run this many MFMAs ahead of their consumer
 #endif
-constexpr int WAIT_VMCNT0 = 0x0F70;  // s_waitcnt vmcnt(0), other counters untouched
-constexpr int WAIT_VMCNT4 = 0x0F74;  // s_waitcnt vmcnt(4): all but the 4 most recent loads have landed
-constexpr int WAIT_VMCNT8 = 0x0F78;  // s_waitcnt vmcnt(8)
+constexpr int wait_vmcnt(int n) { return 0x0F70 | n; }   // s_waitcnt vmcnt(n), n < 16, other counters untouched
+constexpr int WAIT_VMCNT0 = wait_vmcnt(0);
+// end of an iteration: everything but the loads of the last REQ_AHEAD-1 iterations has landed
+constexpr int WAIT_ITER_END = wait_vmcnt((REQ_AHEAD - 1) * 2 * LPT);
 
 struct Params {
     const __bf16 *q, *k, *v;
@@ -77,8 +87,8 @@ struct Params {
     float *lse;
     int B, Hq, Hkv, Sq, Skv;
     int G;          // Hq / Hkv
-    int pack;       // query heads of one K/V group served by one workgroup (1, 2, 4 or 8)
-    int tile_pos;   // query positions per workgroup = 256 / pack
+    int pack;       // query heads of one K/V group served by one workgroup (a power of two <= NWAVES)
+    int tile_pos;   // query positions per workgroup = WG_ROWS / pack
     int ntile;      // ceil(Sq / tile_pos)
     int chunks;     // G / pack
     int total;      // work items = B * Hkv * chunks * ntile
@@ -148,7 +158,7 @@ __device__ __forceinline__ void trace_mark(int &n) {
 #endif
 
 template <bool CAUSAL>
-__global__ __launch_bounds__(NTHREADS) void attn_fwd_kernel(const Params p)
+__global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_fwd_kernel(const Params p)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     LDS_AS unsigned char *lds = (LDS_AS unsigned char *)smem;
@@ -240,15 +250,15 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_kernel(const Params p)
     const unsigned char *kg = (const unsigned char *)(p.k + ((size_t)b * p.Skv * p.Hkv + hkv) * HD);
     const unsigned char *vg = (const unsigned char *)(p.v + ((size_t)b * p.Skv * p.Hkv + hkv) * HD);
     const int ld_r = lane >> 4, ld_u = lane & 15;
-    uint32_t koff[2], voff[2];   // byte offset of this lane's 16 bytes from the first row of a tile
-    int ld_row[2];
+    uint32_t koff[LPT], voff[LPT];   // byte offset of this lane's 16 bytes from the first row of a tile
+    int ld_row[LPT];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        ld_row[i] = (wave * 2 + i) * 4 + ld_r;
+    for (int i = 0; i < LPT; ++i) {
+        ld_row[i] = (wave * LPT + i) * 4 + ld_r;
         koff[i] = (uint32_t)(ld_row[i] * kv_row_bytes) + ((ld_u ^ (ld_row[i] & 15)) << 4);
         voff[i] = (uint32_t)(ld_row[i] * kv_row_bytes) + ((ld_u ^ ((ld_row[i] & 3) << 2)) << 4);
     }
-    const uint32_t lds_wave = (uint32_t)(uintptr_t)lds + wave * 2048;
+    const uint32_t lds_wave = (uint32_t)(uintptr_t)lds + wave * (LPT * 1024);
     auto stage_off = [&](int blk) __attribute__((always_inline)) { return (blk % NSTAGE) * TILE_BYTES; };
     auto next_stage = [&](int o) __attribute__((always_inline)) {      // stage_off(blk + 1) from stage_off(blk)
         return o == (NSTAGE - 1) * TILE_BYTES ? 0 : o + TILE_BYTES;
@@ -262,7 +272,7 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_kernel(const Params p)
         const uint32_t lbase = lds_wave + (is_v ? V_BASE : 0) + stage_off(blk_req);
         const bool partial = (blk + 1) * BN > p.Skv;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < LPT; ++i) {
             uint32_t o = is_v ? voff[i] : koff[i];
             if (partial) {
                 const int rl = min(ld_row[i], p.Skv - 1 - blk * BN);
@@ -468,10 +478,15 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_kernel(const Params p)
                 PIN(pn[k]);
                 lrn = add_bf16_pair(pn[k], lrn);
             }
-            if (slot == 4) lds_dma16(kp, koff[0], lds_wave + kreq);
-            if (slot == 12) lds_dma16(kp, koff[1], lds_wave + kreq + 1024);
-            if (slot == 20) lds_dma16(vp, voff[0], lds_wave + V_BASE + vreq);
-            if (slot == 28) lds_dma16(vp, voff[1], lds_wave + V_BASE + vreq + 1024);
+#pragma unroll
+            for (int n = 0; n < 2 * LPT; ++n) {
+                // with one iteration of notice the requests go out first; otherwise one every few slots
+                const int at = REQ_AHEAD == 1 ? n : 4 + n * (32 / (2 * LPT));
+                if (slot == at) {
+                    if (n < LPT) lds_dma16(kp, koff[n], lds_wave + kreq + n * 1024);
+                    else lds_dma16(vp, voff[n - LPT], lds_wave + V_BASE + vreq + (n - LPT) * 1024);
+                }
+            }
         });
         ls1 += ev[31];
 #pragma unroll
@@ -506,18 +521,30 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_kernel(const Params p)
         // barrier publishes them.
         issue_tile(0, false);
         issue_tile(1, false);
-        issue_tile(2, false);
-        issue_tile(0, true);
-        __builtin_amdgcn_s_waitcnt(WAIT_VMCNT4);          // K(0), K(1) landed
+        if constexpr (REQ_AHEAD >= 2) {
+            issue_tile(2, false);
+            issue_tile(0, true);
+            __builtin_amdgcn_s_waitcnt(wait_vmcnt(2 * LPT));   // K(0), K(1) landed
+        } else {
+            issue_tile(0, true);
+            __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
+        }
         wg_barrier();
         qk_only(sa, stage_off(0));
         qk_only(sb, stage_off(1));
         // P(0): through the masked path, which also handles an empty first block and sets the reference
         softmax_masked(sa, 0);
-        __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);          // K(2), V(0) landed
-        wg_barrier();                                     // and every wavefront is done with K(0), K(1)
-        issue_tile(3, false);                             // the requests of "iteration -1"
-        issue_tile(1, true);
+        if constexpr (REQ_AHEAD >= 2) {
+            __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);      // K(2), V(0) landed
+            wg_barrier();                                 // and every wavefront is done with K(0), K(1)
+            issue_tile(3, false);                         // the requests of "iteration -1"
+            issue_tile(1, true);
+        } else {
+            wg_barrier();                                 // every wavefront is done with K(0), K(1)
+            issue_tile(2, false);
+            __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
+            wg_barrier();
+        }
 
         // Blocks >= n_unm go through the masked softmax, which yields P = 0 where a key is not valid:
         // blocks masked out entirely for this wavefront, and the blocks past the end that the last
@@ -525,38 +552,38 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_kernel(const Params p)
         // MFMA sequences.  Iteration j: scur = S(j+1) (sb for even j), snxt receives S(j+2).
         int j = 0;
         int vst = stage_off(0), kst = stage_off(2);               // stages of V(j), K(j+2)
-        int kreq = stage_off(4), vreq = stage_off(2);             // stages for K(j+4), V(j+2)
+        int kreq = stage_off(2 + REQ_AHEAD), vreq = stage_off(REQ_AHEAD);   // stages for the requests K(j+2+R), V(j+R)
         // Iterations j < fast_end take the fast path: S(j+1) needs no mask, and the tiles requested are
         // full ones (a request past the last block re-reads the last block, which is full here).
-        const int fast_end = all_full ? n_unm - 1 : min(n_unm - 1, nfull - 4);
+        const int fast_end = all_full ? n_unm - 1 : min(n_unm - 1, nfull - (2 + REQ_AHEAD));
         auto tile_ptr = [&](const unsigned char *g, int blk) __attribute__((always_inline)) {
             return g + (size_t)min(blk, nblk - 1) * tile_gbytes;
         };
 #pragma nounroll
         for (; j + 1 < fast_end; j += 2) {
-            fast_iteration(sb, sa, vst, kst, tile_ptr(kg, j + 4), tile_ptr(vg, j + 2), kreq, vreq);
+            fast_iteration(sb, sa, vst, kst, tile_ptr(kg, j + 2 + REQ_AHEAD), tile_ptr(vg, j + REQ_AHEAD), kreq, vreq);
             kreq = next_stage(kreq); vreq = next_stage(vreq);
             vst = next_stage(vst); kst = next_stage(kst);
-            __builtin_amdgcn_s_waitcnt(WAIT_VMCNT4);
+            __builtin_amdgcn_s_waitcnt(WAIT_ITER_END);
             wg_barrier();
-            fast_iteration(sa, sb, vst, kst, tile_ptr(kg, j + 5), tile_ptr(vg, j + 3), kreq, vreq);
+            fast_iteration(sa, sb, vst, kst, tile_ptr(kg, j + 3 + REQ_AHEAD), tile_ptr(vg, j + 1 + REQ_AHEAD), kreq, vreq);
             kreq = next_stage(kreq); vreq = next_stage(vreq);
             vst = next_stage(vst); kst = next_stage(kst);
-            __builtin_amdgcn_s_waitcnt(WAIT_VMCNT4);
+            __builtin_amdgcn_s_waitcnt(WAIT_ITER_END);
             wg_barrier();
         }
 #pragma nounroll
         for (; j < nblk; j += 2) {
             general_iteration(sb, sa, j);
-            issue_tile(j + 4, false);
-            issue_tile(j + 2, true);
-            __builtin_amdgcn_s_waitcnt(WAIT_VMCNT4);
+            issue_tile(j + 2 + REQ_AHEAD, false);
+            issue_tile(j + REQ_AHEAD, true);
+            __builtin_amdgcn_s_waitcnt(WAIT_ITER_END);
             wg_barrier();
             if (j + 1 < nblk) {
                 general_iteration(sa, sb, j + 1);
-                issue_tile(j + 5, false);
-                issue_tile(j + 3, true);
-                __builtin_amdgcn_s_waitcnt(WAIT_VMCNT4);
+                issue_tile(j + 3 + REQ_AHEAD, false);
+                issue_tile(j + 1 + REQ_AHEAD, true);
+                __builtin_amdgcn_s_waitcnt(WAIT_ITER_END);
                 wg_barrier();
             }
         }
@@ -636,7 +663,7 @@ int attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
     p.o = (__bf16 *)o; p.lse = lse;
     p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.Sq = Sq; p.Skv = Skv;
     p.G = Hq / Hkv;
-    p.pack = (p.G % 8 == 0) ? 8 : (p.G % 4 == 0) ? 4 : (p.G % 2 == 0) ? 2 : 1;
+    p.pack = (NWAVES >= 8 && p.G % 8 == 0) ? 8 : (p.G % 4 == 0) ? 4 : (p.G % 2 == 0) ? 2 : 1;
     p.tile_pos = WG_ROWS / p.pack;
     p.ntile = (Sq + p.tile_pos - 1) / p.tile_pos;
     p.chunks = p.G / p.pack;
