@@ -112,6 +112,10 @@ def sample_rows(w, n, seed=None):
     the rest is uniform.
     """
     rng = np.random.default_rng(w.seed * 7919 + 17 if seed is None else seed)
+    total = w.B * w.Hq * w.Sq
+    if n >= total:                      # small problem: every row
+        b, h, i = np.meshgrid(np.arange(w.B), np.arange(w.Hq), np.arange(w.Sq), indexing="ij")
+        return np.stack([b.ravel(), h.ravel(), i.ravel()], axis=1).astype(np.int32)
     rows = set()
     edge_i = {0, 1, 2, w.Sq - 1, w.Sq - 2}
     for base in (0, (w.Sq // 2) // 256 * 256, (w.Sq - 1) // 256 * 256):
@@ -128,7 +132,14 @@ def sample_rows(w, n, seed=None):
         if len(rows) >= n + len(edge_i):
             break
         rows.add((b, h, int(rng.integers(0, w.Sq))))
-    while len(rows) < n:
-        rows.add((int(rng.integers(0, w.B)), int(rng.integers(0, w.Hq)), int(rng.integers(0, w.Sq))))
+    need = n - len(rows)
+    while need > 0:                     # vectorised draws; duplicates are dropped by the set
+        cand = np.stack([rng.integers(0, w.B, 2 * need), rng.integers(0, w.Hq, 2 * need),
+                         rng.integers(0, w.Sq, 2 * need)], axis=1)
+        for t in map(tuple, cand.tolist()):
+            if len(rows) >= n:
+                break
+            rows.add(t)
+        need = n - len(rows)
     out = np.array(sorted(rows), dtype=np.int32)
     return out

@@ -74,3 +74,16 @@ def test_no_cpu_fallback():
 ])
 def test_mfma_probe_bad_arguments(args, code):
     assert A.attn_mfma_probe(*args) == code
+
+
+def test_row_sampler_terminates_and_is_stratified():
+    from paper_2603_24517_amd import workloads as W
+    small = W.WORKLOADS[W.SMALL]
+    every = W.sample_rows(small, 10 ** 6)                      # more rows asked for than exist: all of them, once
+    assert every.shape == (small.B * small.Hq * small.Sq, 3)
+    w = W.WORKLOADS[W.HEADLINE]
+    rows = W.sample_rows(w, 4096)
+    assert len({tuple(r) for r in rows.tolist()}) == len(rows) >= 4096
+    assert {(b, h) for b, h, _ in rows.tolist()} == {(b, h) for b in range(w.B) for h in range(w.Hq)}
+    assert {0, w.Sq - 1} <= set(rows[:, 2].tolist())
+    assert (W.sample_rows(w, 4096) == rows).all()               # seeded
