@@ -77,6 +77,8 @@ constexpr float P_SUM_LIMIT = 16384.0f;
 #define MAT_PREFETCH 3               // LDS reads run this many MFMAs ahead of their consumer
 #endif
 constexpr int wait_vmcnt(int n) { return 0x0F70 | n; }   // s_waitcnt vmcnt(n), n < 16, other counters untouched
+// workgroups that run at the same time on one XCD: 32 CUs, each holding 8 wavefronts of this kernel
+constexpr int WG_SLOTS_PER_XCD = 32 * (8 / NWAVES);
 constexpr int WAIT_VMCNT0 = wait_vmcnt(0);
 // end of an iteration: everything but the loads of the last REQ_AHEAD-1 iterations has landed
 constexpr int WAIT_ITER_END = wait_vmcnt((REQ_AHEAD - 1) * 2 * LPT);
@@ -92,7 +94,12 @@ struct Params {
     int ntile;      // ceil(Sq / tile_pos)
     int chunks;     // G / pack
     int total;      // work items = B * Hkv * chunks * ntile
-    int per_xcd;    // ceil(total / 8)
+    int per_xcd;    // workgroups per XCD (non-causal: ceil(total / 8))
+    // causal only: how the (group, tile) pairs are dealt to the XCDs (a group = one batch entry, K/V head and chunk)
+    int split;      // every group is cut into `split` sub-groups, sub-group r holding the tiles t = r (mod split)
+    int nsub;       // tiles per sub-group = ceil(ntile / split); the padding items exit at once
+    int sgx;        // sub-groups per XCD = groups * split / 8
+    int window;     // sub-groups that one XCD works through together, heaviest tiles of all of them first
     float c;        // scale * log2(e)
 };
 
@@ -143,18 +150,18 @@ __device__ __forceinline__ void wg_barrier() {
 }
 
 #ifdef ATTN_TRACE
-// Debug build only: clock stamps of one workgroup's wavefronts at the start and end of the block loop.
-__device__ unsigned long long g_trace[NWAVES][1024];
-__device__ __forceinline__ void trace_mark(int &n) {
-    if (blockIdx.x == ATTN_TRACE && n < 1024) {
-        const unsigned long long t = __builtin_readcyclecounter();
-        if ((threadIdx.x & 63) == 0) g_trace[threadIdx.x >> 6][n] = t;
-        ++n;
+// Debug build only (-DATTN_TRACE=<workgroups to record>): clock stamps of wavefront 0 of each workgroup
+// at up to seven points of the kernel, and in the last slot the hardware id of where it ran.
+__device__ unsigned long long g_trace[ATTN_TRACE][8];
+__device__ __forceinline__ void trace_mark(int k) {
+    if (blockIdx.x < ATTN_TRACE && threadIdx.x == 0) {
+        g_trace[blockIdx.x][k] = __builtin_readcyclecounter();
+        if (k == 0) g_trace[blockIdx.x][7] = __builtin_amdgcn_s_getreg((31 << 11) | 4);   // HW_ID
     }
 }
-#define TRACE_MARK() do { __builtin_amdgcn_sched_barrier(0); trace_mark(trace_n); __builtin_amdgcn_sched_barrier(0); } while (0)
+#define TRACE_MARK(k) do { __builtin_amdgcn_sched_barrier(0); trace_mark(k); __builtin_amdgcn_sched_barrier(0); } while (0)
 #else
-#define TRACE_MARK() do { } while (0)
+#define TRACE_MARK(k) do { } while (0)
 #endif
 
 template <bool CAUSAL>
@@ -163,18 +170,37 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     LDS_AS unsigned char *lds = (LDS_AS unsigned char *)smem;
 
-    // ---- work item: workgroups are dealt round-robin to the 8 XCDs, so give
-    // each XCD a contiguous range of items (neighbouring items share K/V in
-    // that XCD's L2).
+    // ---- work item: workgroups are dealt round-robin to the 8 XCDs, so XCD x = bid % 8 works through
+    // the list j = bid / 8 = 0, 1, ... in order.  Non-causal: each XCD owns a contiguous range of items
+    // (neighbouring items share K/V in that XCD's L2).  Causal: tiles differ in length, so each XCD owns
+    // whole sub-groups of equal total work and walks `window` of them together from their longest
+    // tiles to their shortest: a CU that drew a long tile is passed by the ones that drew short
+    // tiles, and the list ends on the shortest ones.
+    TRACE_MARK(0);
     const int bid = blockIdx.x;
-    const int item = (bid & 7) * p.per_xcd + (bid >> 3);
-    if (item >= p.total) return;
-    int rem = item;
-    const int tile_r = rem % p.ntile;  rem /= p.ntile;
-    const int chunk = rem % p.chunks;  rem /= p.chunks;
-    const int hkv = rem % p.Hkv;
-    const int b = rem / p.Hkv;
-    const int tile = CAUSAL ? (p.ntile - 1 - tile_r) : tile_r;   // heavy (late) query tiles first
+    int tile, grp;
+    if (CAUSAL) {
+        const int x = bid & 7, j = bid >> 3;
+        const int per_win = p.window * p.nsub;
+        const int w = j / per_win;
+        const int r = j - w * per_win;
+        const int kw = min(p.window, p.sgx - w * p.window);     // the last window may be narrower
+        const int st = r / kw;
+        const int sg = x * p.sgx + w * p.window + (r - st * kw);
+        grp = sg / p.split;
+        const int tile_r = st * p.split + (sg - grp * p.split);
+        if (tile_r >= p.ntile) return;
+        tile = p.ntile - 1 - tile_r;                            // long (late) query tiles first
+    } else {
+        const int item = (bid & 7) * p.per_xcd + (bid >> 3);
+        if (item >= p.total) return;
+        tile = item % p.ntile;
+        grp = item / p.ntile;
+    }
+    const int chunk = grp % p.chunks;
+    const int bh = grp / p.chunks;
+    const int hkv = bh % p.Hkv;
+    const int b = bh / p.Hkv;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -204,9 +230,6 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
     const int nfull = p.Skv / BN;                   // tiles below this index are full
     const bool all_full = (p.Skv % BN) == 0;
 
-#ifdef ATTN_TRACE
-    int trace_n = 0;
-#endif
     // ---- everything the wavefront keeps across the key-block loop
     bf16x8 qf[8];          // Q^T operand: query lane%32, d = 16*s + 8*(lane/32) .. +7
     f32x16 sa[2], sb[2];   // S^T of two blocks in flight (two 32-key tiles each): the softmax consumes one
@@ -513,7 +536,7 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
         if (j + 1 < n_w) softmax_masked(scur, j + 1);
     };
 
-    TRACE_MARK();
+    TRACE_MARK(1);
     if (nblk > 0) {
         // Iteration j reads K(j+2) and V(j) and requests K(j+4) and V(j+2) into the stages of K(j+1)
         // and V(j-1), whose last readers finished before the previous barrier.  It ends by waiting until
@@ -550,6 +573,7 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
         // blocks masked out entirely for this wavefront, and the blocks past the end that the last
         // iterations multiply from stale stages, then contribute nothing, with no branch around the
         // MFMA sequences.  Iteration j: scur = S(j+1) (sb for even j), snxt receives S(j+2).
+        TRACE_MARK(2);
         int j = 0;
         int vst = stage_off(0), kst = stage_off(2);               // stages of V(j), K(j+2)
         int kreq = stage_off(2 + REQ_AHEAD), vreq = stage_off(REQ_AHEAD);   // stages for the requests K(j+2+R), V(j+R)
@@ -572,6 +596,7 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
             __builtin_amdgcn_s_waitcnt(WAIT_ITER_END);
             wg_barrier();
         }
+        TRACE_MARK(3);
 #pragma nounroll
         for (; j < nblk; j += 2) {
             general_iteration(sb, sa, j);
@@ -589,7 +614,7 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
         }
         __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);          // nothing may still be writing LDS at exit
     }
-    TRACE_MARK();
+    TRACE_MARK(4);
 
     // ---- epilogue: O = acc / lr (BF16), LSE = ln2 * (m + log2 l)
     const float lt = lane32_sum(l);
@@ -611,6 +636,7 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
             p.lse[((size_t)b * p.Hq + head) * p.Sq + qrow] = lse;
         }
     }
+    TRACE_MARK(5);
 }
 
 // Measurement aid: a loop of independent 32x32x16 BF16 MFMAs on register operands read once from
@@ -673,6 +699,17 @@ int attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
     if (total + 8 >= INT32_MAX) return ATTN_E_UNSUPPORTED;
     p.total = (int)total;
     p.per_xcd = (int)((total + 7) / 8);
+    p.split = p.nsub = p.sgx = p.window = 1;
+    if (causal) {
+        const int64_t groups = (int64_t)B * Hkv * p.chunks;
+        while ((groups * p.split) % 8 != 0) p.split *= 2;               // 1, 2, 4 or 8
+        p.nsub = (p.ntile + p.split - 1) / p.split;
+        p.sgx = (int)(groups * p.split / 8);
+        while (p.window * 2 <= p.sgx && p.window * p.nsub < WG_SLOTS_PER_XCD) p.window *= 2;
+        const int64_t wgs = (int64_t)p.sgx * p.nsub;
+        if (wgs * 8 + 8 >= INT32_MAX) return ATTN_E_UNSUPPORTED;
+        p.per_xcd = (int)wgs;
+    }
     p.c = scale * 1.4426950408889634f;
 
     // 96 KiB of dynamic LDS needs an opt-in, once per device and kernel.
