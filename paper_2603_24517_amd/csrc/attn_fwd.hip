@@ -53,23 +53,22 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int HD = 128;              // head dimension
 constexpr int BN = 64;               // keys per K/V block
-#ifndef ATTN_NWAVES
-#define ATTN_NWAVES 8
-#endif
-#ifndef ATTN_NSTAGE
-#define ATTN_NSTAGE 3
-#endif
-constexpr int NWAVES = ATTN_NWAVES;  // wavefronts per workgroup: 8 (one workgroup per CU, three LDS stages); 4 with
-                                     // two stages (two workgroups per CU) measures the same and doubles L2 traffic
+constexpr int NWAVES = 8;            // wavefronts per workgroup; one workgroup fills a CU (registers and LDS)
 constexpr int NTHREADS = NWAVES * 64;
 constexpr int WG_ROWS = NWAVES * 32; // query rows per workgroup
 constexpr int ROW_BYTES = HD * 2;    // one (token, head) row of BF16
 constexpr int TILE_BYTES = BN * ROW_BYTES;
-constexpr int NSTAGE = ATTN_NSTAGE;         // LDS stages per operand
+constexpr int NSTAGE = 3;                   // LDS stages per operand
 constexpr int REQ_AHEAD = NSTAGE - 1;       // tiles are requested this many iterations before use
 constexpr int LPT = 16 / NWAVES;            // 1 KiB load instructions per tile and wavefront
 constexpr int V_BASE = NSTAGE * TILE_BYTES; // K stages first, V stages after them
-constexpr int LDS_BYTES = 2 * NSTAGE * TILE_BYTES;
+constexpr int Q_BASE = 2 * NSTAGE * TILE_BYTES;      // after the stages: Q of the next item, 8 KiB per wavefront
+constexpr int Q_WAVE_BYTES = 32 * ROW_BYTES;
+#ifdef ABL_NO_QSTAGE
+constexpr int LDS_BYTES = Q_BASE;
+#else
+constexpr int LDS_BYTES = Q_BASE + NWAVES * Q_WAVE_BYTES;   // 160 KiB, all of a CU's LDS
+#endif
 // Largest partial row sum (16 probabilities of one lane) the fast softmax path accepts: probabilities
 // stay below 2^14 relative to the reference maximum, far inside BF16 / FP32 range.
 constexpr float P_SUM_LIMIT = 16384.0f;
@@ -77,8 +76,6 @@ constexpr float P_SUM_LIMIT = 16384.0f;
 #define MAT_PREFETCH 3               // LDS reads run this many MFMAs ahead of their consumer
 #endif
 constexpr int wait_vmcnt(int n) { return 0x0F70 | n; }   // s_waitcnt vmcnt(n), n < 16, other counters untouched
-// workgroups that run at the same time on one XCD: 32 CUs, each holding 8 wavefronts of this kernel
-constexpr int WG_SLOTS_PER_XCD = 32 * (8 / NWAVES);
 constexpr int WAIT_VMCNT0 = wait_vmcnt(0);
 // end of an iteration: everything but the loads of the last REQ_AHEAD-1 iterations has landed
 constexpr int WAIT_ITER_END = wait_vmcnt((REQ_AHEAD - 1) * 2 * LPT);
@@ -94,12 +91,13 @@ struct Params {
     int ntile;      // ceil(Sq / tile_pos)
     int chunks;     // G / pack
     int total;      // work items = B * Hkv * chunks * ntile
-    int per_xcd;    // workgroups per XCD (non-causal: ceil(total / 8))
+    int per_xcd;    // entries in the work list of one XCD (non-causal: ceil(total / 8))
+    int slots;      // workgroups per XCD in this launch (one per CU); the grid is 8 * slots
     // causal only: how the (group, tile) pairs are dealt to the XCDs (a group = one batch entry, K/V head and chunk)
     int split;      // every group is cut into `split` sub-groups, sub-group r holding the tiles t = r (mod split)
-    int nsub;       // tiles per sub-group = ceil(ntile / split); the padding items exit at once
+    int nsub;       // tiles per sub-group = ceil(ntile / split); the padding entries are skipped
     int sgx;        // sub-groups per XCD = groups * split / 8
-    int window;     // sub-groups that one XCD works through together, heaviest tiles of all of them first
+    int window;     // sub-groups that one XCD works through together, longest tiles of all of them first
     float c;        // scale * log2(e)
 };
 
@@ -129,14 +127,32 @@ __device__ __forceinline__ float max3(float a, float b, float c) {
 // Issued as inline assembly so that the compiler's counter bookkeeping does not make every later
 // LDS read wait for it; the caller waits with s_waitcnt vmcnt(n) before the barrier that publishes
 // the tile.
+// A wave-uniform pointer as a scalar-register pair, also when the compiler chose to keep it in vector registers.
+__device__ __forceinline__ const unsigned char *uniform_ptr(const unsigned char *ptr) {
+    const uint64_t v = (uint64_t)(uintptr_t)ptr;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return (const unsigned char *)(uintptr_t)(((uint64_t)hi << 32) | lo);
+}
 __device__ __forceinline__ void lds_dma16(const unsigned char *base, uint32_t voffset, uint32_t lds_base) {
 #ifdef ABL_NO_DMA
     return;
 #endif
+    base = uniform_ptr(base);
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
                  : "s"(lds_base), "v"(voffset), "s"(base)
                  : "memory");
+}
+// The same with the LDS address given as a scalar plus a compile-time constant (one scalar instruction).
+template <int IMM>
+__device__ __forceinline__ void lds_dma16_imm(const unsigned char *base, uint32_t voffset, uint32_t lds_base) {
+#ifdef ABL_NO_DMA
+    return;
+#endif
+    asm volatile("s_add_u32 m0, %0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_base), "v"(voffset), "s"(base), "n"(IMM)
+                 : "memory", "scc");
 }
 // Keeps the instruction that produces x at this point of the program order (no code is emitted).
 #define PIN(x) asm volatile("" : "+v"(x))
@@ -151,16 +167,26 @@ __device__ __forceinline__ void wg_barrier() {
 
 #ifdef ATTN_TRACE
 // Debug build only (-DATTN_TRACE=<workgroups to record>): clock stamps of wavefront 0 of each workgroup
-// at up to seven points of the kernel, and in the last slot the hardware id of where it ran.
-__device__ unsigned long long g_trace[ATTN_TRACE][8];
-__device__ __forceinline__ void trace_mark(int k) {
-    if (blockIdx.x < ATTN_TRACE && threadIdx.x == 0) {
+// at eight points of its third item (the first two for a workgroup with fewer).
+__device__ unsigned long long g_trace[ATTN_TRACE][12];
+__device__ __forceinline__ void trace_mark(int k, int item) {
+    if (blockIdx.x < ATTN_TRACE && threadIdx.x == 0 && item <= 2)
         g_trace[blockIdx.x][k] = __builtin_readcyclecounter();
-        if (k == 0) g_trace[blockIdx.x][7] = __builtin_amdgcn_s_getreg((31 << 11) | 4);   // HW_ID
-    }
 }
-#define TRACE_MARK(k) do { __builtin_amdgcn_sched_barrier(0); trace_mark(k); __builtin_amdgcn_sched_barrier(0); } while (0)
+#define TRACE_MARK(k) do { __builtin_amdgcn_sched_barrier(0); trace_mark(k, trace_item); __builtin_amdgcn_sched_barrier(0); } while (0)
+#endif
+#if defined(ATTN_TRACE) && defined(ATTN_TRACE_WAIT)
+// cycles the fast loop spends between "MFMA block done" and "barrier passed" (slot 8), in the wait alone (slot 9);
+// reading the clock three times per iteration slows the loop by about 6 %
+#define TRACE_WAIT_BEGIN() do { __builtin_amdgcn_sched_barrier(0); trace_t0 = __builtin_readcyclecounter(); __builtin_amdgcn_sched_barrier(0); } while (0)
+#define TRACE_WAIT_MID() do { __builtin_amdgcn_sched_barrier(0); trace_t1 = __builtin_readcyclecounter(); __builtin_amdgcn_sched_barrier(0); } while (0)
+#define TRACE_WAIT_END() do { __builtin_amdgcn_sched_barrier(0); { const unsigned long long t = __builtin_readcyclecounter(); trace_wait += t - trace_t0; trace_vm += trace_t1 - trace_t0; } __builtin_amdgcn_sched_barrier(0); } while (0)
 #else
+#define TRACE_WAIT_BEGIN() do { } while (0)
+#define TRACE_WAIT_MID() do { } while (0)
+#define TRACE_WAIT_END() do { } while (0)
+#endif
+#ifndef ATTN_TRACE
 #define TRACE_MARK(k) do { } while (0)
 #endif
 
@@ -169,66 +195,116 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     LDS_AS unsigned char *lds = (LDS_AS unsigned char *)smem;
+    // Launch constants that only the per-item code needs are read from the kernel argument block where
+    // they are used, instead of occupying scalar registers through the block loop.
+    auto cold = [&]() __attribute__((always_inline)) -> const __attribute__((address_space(4))) Params & {
+        auto cp = (const __attribute__((address_space(4))) Params *)__builtin_amdgcn_kernarg_segment_ptr();
+        asm volatile("" : "+s"(cp));
+        return *cp;
+    };
 
-    // ---- work item: workgroups are dealt round-robin to the 8 XCDs, so XCD x = bid % 8 works through
-    // the list j = bid / 8 = 0, 1, ... in order.  Non-causal: each XCD owns a contiguous range of items
-    // (neighbouring items share K/V in that XCD's L2).  Causal: tiles differ in length, so each XCD owns
-    // whole sub-groups of equal total work and walks `window` of them together from their longest
-    // tiles to their shortest: a CU that drew a long tile is passed by the ones that drew short
-    // tiles, and the list ends on the shortest ones.
-    TRACE_MARK(0);
+    // ---- work distribution.  The launch has one workgroup per CU, 8 * slots of them, dealt round-robin
+    // to the 8 XCDs by the hardware: workgroup (x = bid % 8, slot = bid / 8) works through entries
+    // slot, slot + slots, ... of XCD x's list, one after the other, so that the loads of the next
+    // entry can start while the current one finishes.
+    // Non-causal: each XCD's list is a contiguous range of items (neighbours share K/V in that XCD's
+    // L2).  Causal: tiles differ in length, so each XCD owns whole sub-groups of equal total work and
+    // its list walks `window` of them together from their longest tiles to their shortest; odd rounds
+    // run through the slots backwards, so that the workgroup that drew the longest tile of one round
+    // draws the shortest of the next.
     const int bid = blockIdx.x;
-    int tile, grp;
-    if (CAUSAL) {
-        const int x = bid & 7, j = bid >> 3;
-        const int per_win = p.window * p.nsub;
-        const int w = j / per_win;
-        const int r = j - w * per_win;
-        const int kw = min(p.window, p.sgx - w * p.window);     // the last window may be narrower
-        const int st = r / kw;
-        const int sg = x * p.sgx + w * p.window + (r - st * kw);
-        grp = sg / p.split;
-        const int tile_r = st * p.split + (sg - grp * p.split);
-        if (tile_r >= p.ntile) return;
-        tile = p.ntile - 1 - tile_r;                            // long (late) query tiles first
-    } else {
-        const int item = (bid & 7) * p.per_xcd + (bid >> 3);
-        if (item >= p.total) return;
-        tile = item % p.ntile;
-        grp = item / p.ntile;
-    }
-    const int chunk = grp % p.chunks;
-    const int bh = grp / p.chunks;
-    const int hkv = bh % p.Hkv;
-    const int b = bh / p.Hkv;
-
+    const int xcd = bid & 7, slot = bid >> 3;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31;
     const int hh = lane >> 5;
-
-    const int head = hkv * p.G + chunk * p.pack + (wave % p.pack);
-    const int q0 = tile * p.tile_pos + (wave / p.pack) * 32;   // first query row of this wave
     const int off = p.Skv - p.Sq;                               // causal: key j valid iff j <= i + off
-
-    // ---- block counts: nblk for the workgroup (one barrier each); n_w of them hold a key that is
-    // valid for some row of this wavefront, and the first n_unm of those need no mask at all.
-    int nblk = (p.Skv + BN - 1) / BN;
-    int n_unm = p.Skv / BN;
-    int n_w = nblk;
-    if (CAUSAL) {
-        const int qlast = min(tile * p.tile_pos + p.tile_pos, p.Sq) - 1;
-        const int klast = qlast + off;
-        nblk = klast < 0 ? 0 : min(nblk, klast / BN + 1);
-        const int klast_w = q0 + 31 + off;          // last key valid for the last row of the wave
-        n_w = klast_w < 0 ? 0 : min(nblk, klast_w / BN + 1);
-        const int kfirst_w = q0 + off + 1;          // number of keys valid for every row of the wave
-        n_unm = min(n_unm, kfirst_w <= 0 ? 0 : kfirst_w / BN);
-    }
-    n_unm = min(n_unm, n_w);
-    const int nfull = p.Skv / BN;                   // tiles below this index are full
+    const int nfull = p.Skv / BN;                               // tiles below this index are full
     const bool all_full = (p.Skv % BN) == 0;
+
+    // entry j of this XCD's list -> (group, tile); false for a padding entry
+    auto decode = [&](int j, int &grp, int &tile) __attribute__((always_inline)) -> bool {
+        if (CAUSAL) {
+            const int per_win = cold().window * cold().nsub;
+            const int w = j / per_win;
+            const int r = j - w * per_win;
+            const int kw = min(cold().window, cold().sgx - w * cold().window);     // the last window may be narrower
+            const int st = r / kw;
+            const int sg = xcd * cold().sgx + w * cold().window + (r - st * kw);
+            grp = sg / cold().split;
+            const int tile_r = st * cold().split + (sg - grp * cold().split);
+            tile = cold().ntile - 1 - tile_r;                            // long (late) query tiles first
+            return tile_r < cold().ntile;
+        }
+        const int item = xcd * cold().per_xcd + j;
+        tile = item % cold().ntile;
+        grp = item / cold().ntile;
+        return item < cold().total;
+    };
+    // first round >= r in which this workgroup has a real entry; false when its list is exhausted
+    auto find_item = [&](int &r, int &grp, int &tile) __attribute__((always_inline)) -> bool {
+        for (; r * cold().slots < cold().per_xcd; ++r) {
+            const int j = r * cold().slots + ((CAUSAL && (r & 1)) ? cold().slots - 1 - slot : slot);
+            if (j < cold().per_xcd && decode(j, grp, tile)) return true;
+        }
+        return false;
+    };
+    // what a wavefront needs to know of an item
+    struct Geo {
+        int b, head, q0;                 // batch entry, query head and first query row of this wavefront
+        int nblk;                        // key blocks of the workgroup (one barrier each)
+        const unsigned char *kg, *vg;    // first K / V row of the item's batch entry and K/V head
+    };
+    const size_t kv_row_bytes = (size_t)p.Hkv * HD * 2;
+    const size_t tile_gbytes = (size_t)BN * kv_row_bytes;
+    auto geometry = [&](int grp, int tile) __attribute__((always_inline)) -> Geo {
+        Geo g;
+        const int chunk = grp % cold().chunks;
+        const int bh = grp / cold().chunks;
+        const int hkv = bh % p.Hkv;
+        g.b = bh / p.Hkv;
+        g.head = hkv * cold().G + chunk * cold().pack + (wave % cold().pack);
+        g.q0 = tile * cold().tile_pos + (wave / cold().pack) * 32;
+        g.nblk = (p.Skv + BN - 1) / BN;
+        if (CAUSAL) {
+            const int klast = min(tile * cold().tile_pos + cold().tile_pos, cold().Sq) - 1 + off;
+            g.nblk = klast < 0 ? 0 : min(g.nblk, klast / BN + 1);
+        }
+        g.kg = (const unsigned char *)(p.k + ((size_t)g.b * p.Skv * p.Hkv + hkv) * HD);
+        g.vg = (const unsigned char *)(p.v + ((size_t)g.b * p.Skv * p.Hkv + hkv) * HD);
+        // all of it is wave-uniform: say so, so that it lives in scalar registers
+        g.b = __builtin_amdgcn_readfirstlane(g.b);
+        g.head = __builtin_amdgcn_readfirstlane(g.head);
+        g.q0 = __builtin_amdgcn_readfirstlane(g.q0);
+        g.nblk = __builtin_amdgcn_readfirstlane(g.nblk);
+        g.kg = uniform_ptr(g.kg);
+        g.vg = uniform_ptr(g.vg);
+        return g;
+    };
+
+    // ---- the item in work and the one after it
+    int b = 0, head = 0, q0 = 0;
+    int nblk = 0;       // key blocks of the workgroup
+    int n_w = 0;        // of those, the blocks that hold a key valid for some row of this wavefront
+    int n_unm = 0;      // of those, the leading blocks that need no mask at all
+    const unsigned char *kg = nullptr, *vg = nullptr;
+    bool warm_next = false;             // the item after this one exists and its first tiles are requested by this one
+    int nx_nblk = 0;
+    const unsigned char *nx_kg = nullptr, *nx_vg = nullptr;
+    int ring0 = 0;                      // LDS stage of block 0 of the item in work
+    auto enter = [&](const Geo &g) __attribute__((always_inline)) {
+        b = g.b; head = g.head; q0 = g.q0; nblk = g.nblk; kg = g.kg; vg = g.vg;
+        n_unm = p.Skv / BN;
+        n_w = nblk;
+        if (CAUSAL) {
+            const int klast_w = q0 + 31 + off;          // last key valid for the last row of the wave
+            n_w = klast_w < 0 ? 0 : min(nblk, klast_w / BN + 1);
+            const int kfirst_w = q0 + off + 1;          // number of keys valid for every row of the wave
+            n_unm = min(n_unm, kfirst_w <= 0 ? 0 : kfirst_w / BN);
+        }
+        n_unm = min(n_unm, n_w);
+    };
 
     // ---- everything the wavefront keeps across the key-block loop
     bf16x8 qf[8];          // Q^T operand: query lane%32, d = 16*s + 8*(lane/32) .. +7
@@ -236,31 +312,44 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
                            // while the MFMAs fill the other
     uint32_t pb[2][8];     // P^T of the block whose PV product comes next, BF16 pairs
     f32x16 acc[4];         // O^T accumulator: four 32-d tiles
-    float m = -INFINITY;   // running maximum in log2 units (score * scale * log2 e)
-    float l = 0.0f;        // this lane's share of the running sum (its 16 of every 32 keys), unrounded FP32
+    float m;               // running maximum in log2 units (score * scale * log2 e)
+    float l;               // this lane's share of the running sum (its 16 of every 32 keys), unrounded FP32
                            // probabilities: the sum LSE is formed from
-    float lr = 0.0f;       // the same sum over the BF16-rounded probabilities that multiply V: O is
+    float lr;              // the same sum over the BF16-rounded probabilities that multiply V: O is
                            // normalised by this one, so that a rounding error in a dominant weight
                            // cancels between numerator and denominator
-    {
-        const int qrow = min(q0 + l32, p.Sq - 1);
-        const __bf16 *qp = p.q + ((size_t)((size_t)b * p.Sq + qrow) * p.Hq + head) * HD + 8 * hh;
+    auto load_q = [&](const Geo &g) __attribute__((always_inline)) {
+        const int qrow = min(g.q0 + l32, cold().Sq - 1);
+        const __bf16 *qp = cold().q + ((size_t)((size_t)g.b * cold().Sq + qrow) * cold().Hq + g.head) * HD + 8 * hh;
 #pragma unroll
         for (int s = 0; s < 8; ++s) qf[s] = *(const bf16x8 *)(qp + 16 * s);
-    }
+    };
+    // The same through LDS: requested (wave-private region, the K swizzle) while the item before is
+    // still in its last iterations, fetched into registers when the item starts.
+    auto request_q = [&](const Geo &g) __attribute__((always_inline)) {
+        const size_t q_row_bytes = (size_t)cold().Hq * HD * 2;
+        const int q0c = min(g.q0, cold().Sq - 1);       // rows past the end of Q re-read the last row
+        const unsigned char *qg = (const unsigned char *)(cold().q + ((size_t)((size_t)g.b * cold().Sq + q0c) * cold().Hq + g.head) * HD);
+        const int last = cold().Sq - 1 - q0c;
+        const uint32_t lbase = (uint32_t)(uintptr_t)lds + Q_BASE + wave * Q_WAVE_BYTES;
+        int ln = lane;
+        PIN(ln);            // per-lane offsets are formed here, not kept in registers across the block loop
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
+        for (int i = 0; i < 8; ++i) {
+            const int row = 4 * i + (ln >> 4);
+            const uint32_t o = (uint32_t)(min(row, last) * q_row_bytes) + (((ln & 15) ^ (row & 15)) << 4);
+            lds_dma16(qg, o, lbase + i * 1024);
+        }
+    };
+    auto reset_state = [&]() __attribute__((always_inline)) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[dt][r] = 0.0f;
+        for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int r = 0; r < 8; ++r) pb[t][r] = 0u;
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) { sa[t][r] = 0.0f; sb[t][r] = 0.0f; }
-
+            for (int r = 0; r < 16; ++r) acc[dt][r] = 0.0f;
+        m = -INFINITY;
+        l = 0.0f;
+        lr = 0.0f;
+    };
     // ---- global -> LDS tile loads.  One instruction moves 1 KiB: lane L's 16
     // bytes land at (wave-uniform LDS base) + 16*L, i.e. row L/16 and physical
     // 16-byte unit L%16 of a 4-row chunk; the lane fetches the logical unit
@@ -268,38 +357,57 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
     // reading one d-range of 16 consecutive rows touch 16 different units.
     // V: unit ^ ((row & 3) << 2), so that the 4 rows x 64 bytes a half-wave
     // fetches with the transposing read cover all banks once.
-    const size_t kv_row_bytes = (size_t)p.Hkv * HD * 2;
-    const size_t tile_gbytes = (size_t)BN * kv_row_bytes;
-    const unsigned char *kg = (const unsigned char *)(p.k + ((size_t)b * p.Skv * p.Hkv + hkv) * HD);
-    const unsigned char *vg = (const unsigned char *)(p.v + ((size_t)b * p.Skv * p.Hkv + hkv) * HD);
     const int ld_r = lane >> 4, ld_u = lane & 15;
     uint32_t koff[LPT], voff[LPT];   // byte offset of this lane's 16 bytes from the first row of a tile
-    int ld_row[LPT];
 #pragma unroll
     for (int i = 0; i < LPT; ++i) {
-        ld_row[i] = (wave * LPT + i) * 4 + ld_r;
-        koff[i] = (uint32_t)(ld_row[i] * kv_row_bytes) + ((ld_u ^ (ld_row[i] & 15)) << 4);
-        voff[i] = (uint32_t)(ld_row[i] * kv_row_bytes) + ((ld_u ^ ((ld_row[i] & 3) << 2)) << 4);
+        const int row = (wave * LPT + i) * 4 + ld_r;
+        koff[i] = (uint32_t)(row * kv_row_bytes) + ((ld_u ^ (row & 15)) << 4);
+        voff[i] = (uint32_t)(row * kv_row_bytes) + ((ld_u ^ ((row & 3) << 2)) << 4);
     }
     const uint32_t lds_wave = (uint32_t)(uintptr_t)lds + wave * (LPT * 1024);
-    auto stage_off = [&](int blk) __attribute__((always_inline)) { return (blk % NSTAGE) * TILE_BYTES; };
+    // The three stages are a ring that runs on from one item to the next: block j of the item in work
+    // lives in stage (ring0 + j) % 3, and blocks nblk, nblk+1, ... are blocks 0, 1, ... of the next item.
+#ifdef ABL_ONE_STAGE
+    auto stage_off = [&](int) __attribute__((always_inline)) { return 0; };
+#else
+    auto stage_off = [&](int blk) __attribute__((always_inline)) { return ((blk + ring0) % NSTAGE) * TILE_BYTES; };
+#endif
     auto next_stage = [&](int o) __attribute__((always_inline)) {      // stage_off(blk + 1) from stage_off(blk)
+#ifdef ABL_ONE_STAGE
+        return o;
+#endif
         return o == (NSTAGE - 1) * TILE_BYTES ? 0 : o + TILE_BYTES;
     };
-    // General form: a request past the last block re-reads the last block into the (dead) stage it
-    // would have used, so the number of loads in flight is the same in every iteration; rows past
-    // the end of a partial tile re-read the last row (they are masked later).
+    // Global address of the tile that request `blk_req` stands for: a block of this item, or (past its
+    // end) a block of the next item if that one is being warmed up; otherwise, and past the end of
+    // the next item too, the last block is read again into the (dead) stage the request would have
+    // used, so that the number of loads in flight is the same in every iteration.
+    auto tile_ptr = [&](int blk_req, bool is_v, int &blk) __attribute__((always_inline)) -> const unsigned char * {
+        const unsigned char *g = is_v ? vg : kg;
+        blk = min(blk_req, nblk - 1);
+        if (blk_req >= nblk && warm_next) {
+            g = is_v ? nx_vg : nx_kg;
+            blk = min(blk_req - nblk, nx_nblk - 1);
+        }
+        return g + (size_t)blk * tile_gbytes;
+    };
+    // General form of a tile request: rows past the end of a partial tile re-read the last row (they
+    // are masked later).
     auto issue_tile = [&](int blk_req, bool is_v) __attribute__((always_inline)) {
-        const int blk = min(blk_req, nblk - 1);
-        const unsigned char *g = (is_v ? vg : kg) + (size_t)blk * tile_gbytes;
+        int blk;
+        const unsigned char *g = tile_ptr(blk_req, is_v, blk);
         const uint32_t lbase = lds_wave + (is_v ? V_BASE : 0) + stage_off(blk_req);
         const bool partial = (blk + 1) * BN > p.Skv;
 #pragma unroll
         for (int i = 0; i < LPT; ++i) {
             uint32_t o = is_v ? voff[i] : koff[i];
             if (partial) {
-                const int rl = min(ld_row[i], p.Skv - 1 - blk * BN);
-                o = o - (uint32_t)(ld_row[i] * kv_row_bytes) + (uint32_t)(rl * kv_row_bytes);
+                int ln = lane;
+                PIN(ln);        // formed here, not kept in a register across the block loop
+                const int row = (wave * LPT + i) * 4 + (ln >> 4);
+                const int rl = min(row, p.Skv - 1 - blk * BN);
+                o = o - (uint32_t)(row * kv_row_bytes) + (uint32_t)(rl * kv_row_bytes);
             }
             lds_dma16(g, o, lbase + i * 1024);
         }
@@ -432,9 +540,11 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
     // wholly past this wavefront's rows): key index per register, limit per lane.  Masked keys get
     // P = 0 exactly, whatever the score registers hold.
     auto softmax_masked = [&](f32x16 (&s)[2], int blk) __attribute__((always_inline)) {
+        int ln = lane;
+        PIN(ln);                // lane-derived values are formed here, not kept across the block loop
         int lim = p.Skv - 1;
-        if (CAUSAL) lim = min(lim, q0 + l32 + off);
-        const int kidx = blk * BN + 4 * hh;
+        if (CAUSAL) lim = min(lim, q0 + (ln & 31) + off);
+        const int kidx = blk * BN + 4 * (ln >> 5);
         float mx = -INFINITY;
 #pragma unroll
         for (int t = 0; t < 2; ++t)
@@ -477,13 +587,16 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
     // The iteration's four tile requests (K(j+4) from kp into stage kreq, V(j+2) from vp into stage vreq)
     // are spread over the block, one every eight slots, so that the wavefronts' requests do not queue up
     // behind each other in the address unit.
-    auto fast_iteration = [&](f32x16 (&scur)[2], f32x16 (&snxt)[2], int vb, int kb,
-                              const unsigned char *kp, const unsigned char *vp, int kreq, int vreq)
+    // s0, s1, s2: stages of blocks j, j+1, j+2 (V is read from s0, K from s2; the requests go to s1 for K
+    // and s2 for V).
+    auto fast_iteration = [&](f32x16 (&scur)[2], f32x16 (&snxt)[2], int s0, int s1, int s2,
+                              const unsigned char *kp, const unsigned char *vp)
         __attribute__((always_inline)) {
         float ev[32];
         uint32_t pn[16];
         float ls0 = 0.0f, ls1 = 0.0f, lrn = 0.0f;
-        mfma_block(snxt, vb, kb, [&](int slot) __attribute__((always_inline)) {
+        const uint32_t klds = lds_wave + s1, vlds = lds_wave + V_BASE + s2;
+        mfma_block(snxt, s0, s2, [&](int slot) __attribute__((always_inline)) {
             // element `slot` of the 32 scores of this lane: exp now, row-sum add one slot later
 #ifdef ABL_NO_EXP
             ev[slot] = __builtin_fmaf(scur[slot >> 4][slot & 15], p.c, -m);
@@ -501,15 +614,11 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
                 PIN(pn[k]);
                 lrn = add_bf16_pair(pn[k], lrn);
             }
-#pragma unroll
-            for (int n = 0; n < 2 * LPT; ++n) {
-                // with one iteration of notice the requests go out first; otherwise one every few slots
-                const int at = REQ_AHEAD == 1 ? n : 4 + n * (32 / (2 * LPT));
-                if (slot == at) {
-                    if (n < LPT) lds_dma16(kp, koff[n], lds_wave + kreq + n * 1024);
-                    else lds_dma16(vp, voff[n - LPT], lds_wave + V_BASE + vreq + (n - LPT) * 1024);
-                }
-            }
+            static_assert(LPT == 2, "request slots below are written out for two loads per tile and wavefront");
+            if (slot == 4) lds_dma16_imm<0>(kp, koff[0], klds);
+            if (slot == 12) lds_dma16_imm<1024>(kp, koff[1], klds);
+            if (slot == 20) lds_dma16_imm<0>(vp, voff[0], vlds);
+            if (slot == 28) lds_dma16_imm<1024>(vp, voff[1], vlds);
         });
         ls1 += ev[31];
 #pragma unroll
@@ -536,107 +645,217 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
         if (j + 1 < n_w) softmax_masked(scur, j + 1);
     };
 
-    TRACE_MARK(1);
-    if (nblk > 0) {
-        // Iteration j reads K(j+2) and V(j) and requests K(j+4) and V(j+2) into the stages of K(j+1)
-        // and V(j-1), whose last readers finished before the previous barrier.  It ends by waiting until
-        // only those four loads are still in flight, i.e. until K(j+3) and V(j+1) have landed, then the
-        // barrier publishes them.
-        issue_tile(0, false);
-        issue_tile(1, false);
-        if constexpr (REQ_AHEAD >= 2) {
-            issue_tile(2, false);
-            issue_tile(0, true);
-            __builtin_amdgcn_s_waitcnt(wait_vmcnt(2 * LPT));   // K(0), K(1) landed
-        } else {
-            issue_tile(0, true);
-            __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
-        }
-        wg_barrier();
-        qk_only(sa, stage_off(0));
-        qk_only(sb, stage_off(1));
-        // P(0): through the masked path, which also handles an empty first block and sets the reference
-        softmax_masked(sa, 0);
-        if constexpr (REQ_AHEAD >= 2) {
-            __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);      // K(2), V(0) landed
+    // ---- the workgroup's items, one after the other
+    int r = 0, grp = 0, tile = 0;
+    bool have = find_item(r, grp, tile);
+    Geo cur = {};
+    if (have) {
+        cur = geometry(grp, tile);
+        load_q(cur);
+    }
+#ifdef ATTN_TRACE
+    int trace_item = 0;
+    unsigned long long trace_t0 = 0, trace_t1 = 0, trace_wait = 0, trace_vm = 0;
+#endif
+    bool warm = false;          // the first tiles of the item about to start were requested by the item before it
+    while (have) {
+        TRACE_MARK(0);
+        enter(cur);
+        reset_state();
+        // the item after this one
+        Geo nxt = cur;
+        int r2 = r + 1;
+        const bool have2 = find_item(r2, grp, tile);
+        if (have2) nxt = geometry(grp, tile);
+        // Its tiles K'(0..2), V'(0) ride on this item's last iterations (requests K(j+4), V(j+2) of
+        // iterations j >= nblk-4), which takes four iterations to host them.
+        warm_next = have2 && nblk >= 2 + REQ_AHEAD && nxt.nblk > 0;
+        nx_nblk = nxt.nblk; nx_kg = nxt.kg; nx_vg = nxt.vg;
+
+        TRACE_MARK(1);
+        if (nblk > 0) {
+            // Iteration j reads K(j+2) and V(j) and requests K(j+4) and V(j+2) into the stages of K(j+1)
+            // and V(j-1), whose last readers finished before the previous barrier.  It ends by waiting until
+            // only those four loads are still in flight, i.e. until K(j+3) and V(j+1) have landed, then the
+            // barrier publishes them.
+            if (!warm) {
+                // Every wavefront is past the last barrier of the item before, so no stage is being read.
+                issue_tile(0, false);
+                issue_tile(1, false);
+                issue_tile(2, false);
+                issue_tile(0, true);
+                __builtin_amdgcn_s_waitcnt(wait_vmcnt(2 * LPT));   // K(0), K(1) landed
+                wg_barrier();
+            }
+            // warm: K(0..2), V(0) and this wavefront's Q landed before the last barrier of the item before
+#ifndef ABL_NO_QSTAGE
+            if (warm) {
+#pragma unroll
+                for (int s = 0; s < 8; ++s)
+                    qf[s] = *(const LDS_AS bf16x8 *)(lds + Q_BASE + wave * Q_WAVE_BYTES + kaddr[s]);
+            }
+#endif
+            qk_only(sa, stage_off(0));
+            qk_only(sb, stage_off(1));
+            TRACE_MARK(2);
+            // P(0): through the masked path, which also handles an empty first block and sets the reference
+            softmax_masked(sa, 0);
+            TRACE_MARK(3);
+            if (!warm) __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);   // K(2), V(0) landed
             wg_barrier();                                 // and every wavefront is done with K(0), K(1)
             issue_tile(3, false);                         // the requests of "iteration -1"
             issue_tile(1, true);
-        } else {
-            wg_barrier();                                 // every wavefront is done with K(0), K(1)
-            issue_tile(2, false);
-            __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
-            wg_barrier();
-        }
+            TRACE_MARK(4);
 
-        // Blocks >= n_unm go through the masked softmax, which yields P = 0 where a key is not valid:
-        // blocks masked out entirely for this wavefront, and the blocks past the end that the last
-        // iterations multiply from stale stages, then contribute nothing, with no branch around the
-        // MFMA sequences.  Iteration j: scur = S(j+1) (sb for even j), snxt receives S(j+2).
-        TRACE_MARK(2);
-        int j = 0;
-        int vst = stage_off(0), kst = stage_off(2);               // stages of V(j), K(j+2)
-        int kreq = stage_off(2 + REQ_AHEAD), vreq = stage_off(REQ_AHEAD);   // stages for the requests K(j+2+R), V(j+R)
-        // Iterations j < fast_end take the fast path: S(j+1) needs no mask, and the tiles requested are
-        // full ones (a request past the last block re-reads the last block, which is full here).
-        const int fast_end = all_full ? n_unm - 1 : min(n_unm - 1, nfull - (2 + REQ_AHEAD));
-        auto tile_ptr = [&](const unsigned char *g, int blk) __attribute__((always_inline)) {
-            return g + (size_t)min(blk, nblk - 1) * tile_gbytes;
-        };
+            // Blocks >= n_unm go through the masked softmax, which yields P = 0 where a key is not valid:
+            // blocks masked out entirely for this wavefront, and the blocks past the end that the last
+            // iterations multiply from stages that hold other tiles, then contribute nothing, with no
+            // branch around the MFMA sequences.  Iteration j: scur = S(j+1) (sb for even j), snxt
+            // receives S(j+2).
+            int j = 0;
+            // Iterations j < fast_end take the fast path: S(j+1) needs no mask, and the tiles requested are
+            // full ones (past the last block: of the next item, or the last block again).
+            int fast_end = all_full ? n_unm - 1 : min(n_unm - 1, nfull - (2 + REQ_AHEAD));
+            // the last two iterations of an item that warms up the next one have extra duties (below)
+            if (warm_next) fast_end = min(fast_end, nblk - 2);
+            // Request addresses of the fast loop.  K and V have the same shape, so V's address is K's of
+            // two iterations earlier plus the distance between the tensors; K's moves on by one tile per
+            // iteration, except at the item's last block (on to block 0 of the next item, or stay) and,
+            // if there is no next item, after it (stay).
+            const ptrdiff_t dv = (const unsigned char *)p.v - (const unsigned char *)p.k;
+            int unused;
+            const unsigned char *kp = uniform_ptr(tile_ptr(2 + REQ_AHEAD, false, unused));
+            const unsigned char *vp = uniform_ptr(tile_ptr(REQ_AHEAD, true, unused));
+            const unsigned char *vp1 = uniform_ptr(tile_ptr(1 + REQ_AHEAD, true, unused));
+            int kleft = nblk - 1 - (2 + REQ_AHEAD);      // whole-tile steps left before K's request reaches the last block
+            const ptrdiff_t kjump = warm_next ? nx_kg - (kg + (size_t)(nblk - 1) * tile_gbytes) : 0;
+            const ptrdiff_t kafter = warm_next ? (ptrdiff_t)tile_gbytes : 0;
+            // (written out twice below rather than as a lambda: selecting between captured variables
+            // would keep them in memory)
+#define ATTN_ADVANCE_REQUESTS()                                                              \
+            do {                                                                             \
+                ptrdiff_t step = kleft < 0 ? kafter : kjump;                                 \
+                step = kleft > 0 ? (ptrdiff_t)tile_gbytes : step;                            \
+                vp = vp1;                                                                    \
+                vp1 = kp + dv;                                                               \
+                kp += step;                                                                  \
+                --kleft;                                                                     \
+            } while (0)
+            int s0 = stage_off(0), s1 = stage_off(1), s2 = stage_off(2);
 #pragma nounroll
-        for (; j + 1 < fast_end; j += 2) {
-            fast_iteration(sb, sa, vst, kst, tile_ptr(kg, j + 2 + REQ_AHEAD), tile_ptr(vg, j + REQ_AHEAD), kreq, vreq);
-            kreq = next_stage(kreq); vreq = next_stage(vreq);
-            vst = next_stage(vst); kst = next_stage(kst);
-            __builtin_amdgcn_s_waitcnt(WAIT_ITER_END);
-            wg_barrier();
-            fast_iteration(sa, sb, vst, kst, tile_ptr(kg, j + 3 + REQ_AHEAD), tile_ptr(vg, j + 1 + REQ_AHEAD), kreq, vreq);
-            kreq = next_stage(kreq); vreq = next_stage(vreq);
-            vst = next_stage(vst); kst = next_stage(kst);
-            __builtin_amdgcn_s_waitcnt(WAIT_ITER_END);
-            wg_barrier();
-        }
-        TRACE_MARK(3);
-#pragma nounroll
-        for (; j < nblk; j += 2) {
-            general_iteration(sb, sa, j);
-            issue_tile(j + 2 + REQ_AHEAD, false);
-            issue_tile(j + REQ_AHEAD, true);
-            __builtin_amdgcn_s_waitcnt(WAIT_ITER_END);
-            wg_barrier();
-            if (j + 1 < nblk) {
-                general_iteration(sa, sb, j + 1);
-                issue_tile(j + 3 + REQ_AHEAD, false);
-                issue_tile(j + 1 + REQ_AHEAD, true);
+            for (; j + 1 < fast_end; j += 2) {
+                fast_iteration(sb, sa, s0, s1, s2, kp, vp);
+                ATTN_ADVANCE_REQUESTS();
+                TRACE_WAIT_BEGIN();
                 __builtin_amdgcn_s_waitcnt(WAIT_ITER_END);
+                TRACE_WAIT_MID();
                 wg_barrier();
+                TRACE_WAIT_END();
+                fast_iteration(sa, sb, s1, s2, s0, kp, vp);
+                ATTN_ADVANCE_REQUESTS();
+                { const int t = s0; s0 = s2; s2 = s1; s1 = t; }
+                TRACE_WAIT_BEGIN();
+                __builtin_amdgcn_s_waitcnt(WAIT_ITER_END);
+                TRACE_WAIT_MID();
+                wg_barrier();
+                TRACE_WAIT_END();
             }
+#undef ATTN_ADVANCE_REQUESTS
+            TRACE_MARK(5);
+            // An item that warms up the next one: its iteration nblk-2 also requests the next Q into this
+            // wavefront's LDS region (after its tile requests, so it may leave those eight loads in
+            // flight too), and its last iteration requests nothing (K'(3) would land in the stage of
+            // K'(0), which is read only after this item's last barrier) and waits for everything.
+            auto iteration_end = [&](int jj) __attribute__((always_inline)) {
+                if (warm_next && jj >= nblk - 2) {
+                    if (jj == nblk - 2) {
+                        issue_tile(jj + 2 + REQ_AHEAD, false);
+                        issue_tile(jj + REQ_AHEAD, true);
+#ifdef ABL_NO_QSTAGE
+                        __builtin_amdgcn_s_waitcnt(WAIT_ITER_END);
+#else
+                        request_q(nxt);
+                        __builtin_amdgcn_s_waitcnt(wait_vmcnt(2 * LPT + 8));
+#endif
+                    } else {
+                        __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
+                    }
+                } else {
+                    issue_tile(jj + 2 + REQ_AHEAD, false);
+                    issue_tile(jj + REQ_AHEAD, true);
+                    __builtin_amdgcn_s_waitcnt(WAIT_ITER_END);
+                }
+                wg_barrier();
+            };
+#pragma nounroll
+            for (; j < nblk; j += 2) {
+                general_iteration(sb, sa, j);
+                iteration_end(j);
+                if (j + 1 < nblk) {
+                    general_iteration(sa, sb, j + 1);
+                    iteration_end(j + 1);
+                }
+            }
+            if (!warm_next) __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);   // nothing may still be writing LDS at exit
         }
-        __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);          // nothing may still be writing LDS at exit
-    }
-    TRACE_MARK(4);
+        TRACE_MARK(6);
 
-    // ---- epilogue: O = acc / lr (BF16), LSE = ln2 * (m + log2 l)
-    const float lt = lane32_sum(l);
-    const float lrt = lane32_sum(lr);
-    const float inv = lrt > 0.0f ? 1.0f / lrt : 0.0f;
-    const int qrow = q0 + l32;
-    if (qrow < p.Sq) {
-        __bf16 *op = p.o + ((size_t)((size_t)b * p.Sq + qrow) * p.Hq + head) * HD + 4 * hh;
+        // ---- epilogue: O = acc / lr (BF16), LSE = ln2 * (m + log2 l).  A lane holds one query's values
+        // in pieces of 8 bytes; they go through LDS (two halves of 64 d, 4 KiB per wavefront, in the two
+        // V stages that hold no tile of the next item: those of blocks nblk+1 and nblk+2 of the ring),
+        // so that each store instruction writes whole 128-byte lines.
+#ifdef ABL_NO_QSTAGE
+        if (have2) load_q(nxt);
+#else
+        if (have2 && !warm_next) load_q(nxt);      // not warmed up: straight from memory, behind the epilogue
+#endif
+        const float lt = lane32_sum(l);
+        const float lrt = lane32_sum(lr);
+        const float inv = lrt > 0.0f ? 1.0f / lrt : 0.0f;
+        {
+            const int ob = V_BASE + stage_off(nblk + 1 + (wave >> 2)) + (wave & 3) * 4096;
+            int ln = lane;
+            PIN(ln);        // per-lane offsets are formed here, not kept in registers across the block loop
+            const int orow = ln >> 3, ounit = ln & 7, l32 = ln & 31, hh = ln >> 5;
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
+            for (int half = 0; half < 2; ++half) {
 #pragma unroll
-            for (int rg = 0; rg < 4; ++rg) {
-                u32x2 ww = {pack_bf16(acc[dt][4 * rg] * inv, acc[dt][4 * rg + 1] * inv),
-                            pack_bf16(acc[dt][4 * rg + 2] * inv, acc[dt][4 * rg + 3] * inv)};
-                *(u32x2 *)(op + 32 * dt + 8 * rg) = ww;
+                for (int dtl = 0; dtl < 2; ++dtl)
+#pragma unroll
+                    for (int rg = 0; rg < 4; ++rg) {
+                        const int dt = 2 * half + dtl;
+                        u32x2 ww = {pack_bf16(acc[dt][4 * rg] * inv, acc[dt][4 * rg + 1] * inv),
+                                    pack_bf16(acc[dt][4 * rg + 2] * inv, acc[dt][4 * rg + 3] * inv)};
+                        *(LDS_AS u32x2 *)(lds + ob + l32 * 128 + (((4 * dtl + rg) ^ (l32 & 7)) << 4) + 8 * hh) = ww;
+                    }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int row = 8 * i + orow;
+                    const u32x4 val = *(const LDS_AS u32x4 *)(lds + ob + row * 128 + ((ounit ^ (row & 7)) << 4));
+                    const int qrow = q0 + row;
+                    if (qrow < cold().Sq)
+                        *(u32x4 *)(cold().o + ((size_t)((size_t)b * cold().Sq + qrow) * cold().Hq + head) * HD + 64 * half + 8 * ounit) = val;
+                }
             }
-        if (hh == 0) {
-            const float lse = lt > 0.0f ? (m + __builtin_amdgcn_logf(lt)) * 0.6931471805599453f : -INFINITY;
-            p.lse[((size_t)b * p.Hq + head) * p.Sq + qrow] = lse;
+            const int qrow = q0 + l32;
+            if (qrow < cold().Sq && hh == 0) {
+                const float lse = lt > 0.0f ? (m + __builtin_amdgcn_logf(lt)) * 0.6931471805599453f : -INFINITY;
+                cold().lse[((size_t)b * cold().Hq + head) * cold().Sq + qrow] = lse;
+            }
         }
+        TRACE_MARK(7);
+#ifdef ATTN_TRACE
+        if (blockIdx.x < ATTN_TRACE && threadIdx.x == 0 && trace_item <= 2) { g_trace[blockIdx.x][8] = trace_wait; g_trace[blockIdx.x][9] = trace_vm; }
+        trace_wait = 0; trace_vm = 0;
+        ++trace_item;
+#endif
+
+        ring0 = (ring0 + nblk) % NSTAGE;
+        warm = warm_next;
+        have = have2;
+        r = r2;
+        cur = nxt;
     }
-    TRACE_MARK(5);
 }
 
 // Measurement aid: a loop of independent 32x32x16 BF16 MFMAs on register operands read once from
@@ -698,6 +917,24 @@ int attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
     const int64_t total = (int64_t)B * Hkv * p.chunks * p.ntile;
     if (total + 8 >= INT32_MAX) return ATTN_E_UNSUPPORTED;
     p.total = (int)total;
+    p.c = scale * 1.4426950408889634f;
+
+    // Once per device: the CU count, and the opt-in that 96 KiB of dynamic LDS needs.
+    static int cus[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return ATTN_E_LAUNCH;
+    if (!cus[dev]) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0 ||
+            hipFuncSetAttribute((const void *)attn_fwd_kernel<true>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess ||
+            hipFuncSetAttribute((const void *)attn_fwd_kernel<false>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess)
+            return ATTN_E_LAUNCH;
+        cus[dev] = n;
+    }
+    // One workgroup per CU (a workgroup takes all of a CU's registers), each working through a list.
+    const int cu_slots = cus[dev] >= 8 ? cus[dev] / 8 : 1;
     p.per_xcd = (int)((total + 7) / 8);
     p.split = p.nsub = p.sgx = p.window = 1;
     if (causal) {
@@ -705,28 +942,13 @@ int attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
         while ((groups * p.split) % 8 != 0) p.split *= 2;               // 1, 2, 4 or 8
         p.nsub = (p.ntile + p.split - 1) / p.split;
         p.sgx = (int)(groups * p.split / 8);
-        while (p.window * 2 <= p.sgx && p.window * p.nsub < WG_SLOTS_PER_XCD) p.window *= 2;
-        const int64_t wgs = (int64_t)p.sgx * p.nsub;
-        if (wgs * 8 + 8 >= INT32_MAX) return ATTN_E_UNSUPPORTED;
-        p.per_xcd = (int)wgs;
+        while (p.window * 2 <= p.sgx && p.window * p.nsub < cu_slots) p.window *= 2;
+        const int64_t entries = (int64_t)p.sgx * p.nsub;
+        if (entries * 8 + 8 >= INT32_MAX) return ATTN_E_UNSUPPORTED;
+        p.per_xcd = (int)entries;
     }
-    p.c = scale * 1.4426950408889634f;
-
-    // 96 KiB of dynamic LDS needs an opt-in, once per device and kernel.
-    {
-        static bool ready[64] = {};
-        int dev = 0;
-        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return ATTN_E_LAUNCH;
-        if (!ready[dev]) {
-            if (hipFuncSetAttribute((const void *)attn_fwd_kernel<true>,
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess ||
-                hipFuncSetAttribute((const void *)attn_fwd_kernel<false>,
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess)
-                return ATTN_E_LAUNCH;
-            ready[dev] = true;
-        }
-    }
-    const dim3 grid((unsigned)(p.per_xcd * 8)), block(NTHREADS);
+    p.slots = p.per_xcd < cu_slots ? p.per_xcd : cu_slots;
+    const dim3 grid((unsigned)(p.slots * 8)), block(NTHREADS);
     hipStream_t st = (hipStream_t)stream;
     if (causal)
         hipLaunchKernelGGL(attn_fwd_kernel<true>, grid, block, LDS_BYTES, st, p);

@@ -201,3 +201,41 @@ def test_huge_scores_overflow_exp():
     """Scores of several hundred: exp2 of the first guess overflows to inf, the exact path must take over."""
     q, k, v = U.rand_qkv(1, 2, 2, 640, 1024, seed=33, q_mul=64.0)
     U.check_full(q, k, v, False, 1.0, what="huge scores")
+
+
+# More work items than the launch has workgroups (one per CU, 256): every workgroup works through a
+# list, and the tiles and Q of an item are requested while the item before it is still in its last
+# blocks.  Shapes: (B, Hq, Hkv, Sq, Skv); what each one exercises is named beside it.
+MANY_ITEMS = [
+    (9, 16, 16, 520, 520),     # 432 items of 9 blocks: second round half full, ragged last tile
+    (3, 40, 40, 777, 777),     # 480 items, partial last key block on every item
+    (8, 32, 8, 300, 300),      # group of 4 heads packed into a workgroup, 5 blocks per item
+    (5, 64, 8, 260, 260),      # group of 8 packed, 32 positions per item
+    (4, 24, 24, 900, 500),     # causal: leading tiles without any valid key between regular ones
+    (4, 24, 24, 520, 1100),    # causal with more keys than queries
+    (16, 32, 32, 128, 128),    # two blocks per item: too short to carry the next item's requests
+    (4, 64, 64, 960, 960),     # four rounds, every tile full
+    (3, 5, 5, 5000, 5000),     # 15 heads: causal tiles split eight ways over the XCDs
+    (2, 6, 2, 4100, 4100),     # 4 groups after packing 3 heads singly: split two ways
+]
+
+
+@pytest.mark.parametrize("causal", [False, True], ids=["full", "causal"])
+@pytest.mark.parametrize("shape", MANY_ITEMS, ids=lambda s: "x".join(map(str, s)))
+def test_many_items_per_workgroup(shape, causal):
+    B, Hq, Hkv, Sq, Skv = shape
+    q, k, v = U.rand_qkv(B, Hq, Hkv, Sq, Skv, seed=7000 + hash(shape) % 1000)
+    print(f"case shape={shape} causal={causal}", flush=True)
+    U.check_full(q, k, v, causal, SCALE, what=f"{shape} causal={causal}")
+
+
+def test_back_to_back_launches_of_different_shapes():
+    """LDS and registers carry nothing from one launch to the next: alternate two shapes, compare each time."""
+    a = U.rand_qkv(6, 16, 16, 600, 600, seed=7101)
+    b = U.rand_qkv(2, 8, 2, 333, 1000, seed=7102)
+    ref_a = oracle.attn_ref(*a, True, SCALE)
+    ref_b = oracle.attn_ref(*b, False, SCALE)
+    for n in range(3):
+        print(f"round {n}", flush=True)
+        U.compare(*U.run_gpu(*a, True, SCALE), *ref_a, what=f"A round {n}")
+        U.compare(*U.run_gpu(*b, False, SCALE), *ref_b, what=f"B round {n}")
