@@ -35,6 +35,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <math.h>
+#include <type_traits>
 
 #include "../../include/attn.h"
 
@@ -589,13 +590,27 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
     // behind each other in the address unit.
     // s0, s1, s2: stages of blocks j, j+1, j+2 (V is read from s0, K from s2; the requests go to s1 for K
     // and s2 for V).
-    auto fast_iteration = [&](f32x16 (&scur)[2], f32x16 (&snxt)[2], int s0, int s1, int s2,
-                              const unsigned char *kp, const unsigned char *vp)
+    // The masked form (diagonal blocks, the partial last block, blocks past the end) does the same with
+    // every probability whose key is not valid for the lane's row set to zero, whatever its score
+    // register holds; its second pass is the masked softmax, which also copes with a row that has no
+    // valid key so far (reference at minus infinity).  It issues no requests: those go through the
+    // general form after the block.
+    auto fused_iteration = [&](auto masked, f32x16 (&scur)[2], f32x16 (&snxt)[2], int s0, int s1, int s2,
+                               const unsigned char *kp, const unsigned char *vp, int blk)
         __attribute__((always_inline)) {
+        constexpr bool MASKED = decltype(masked)::value;
         float ev[32];
         uint32_t pn[16];
         float ls0 = 0.0f, ls1 = 0.0f, lrn = 0.0f;
         const uint32_t klds = lds_wave + s1, vlds = lds_wave + V_BASE + s2;
+        int room = 0;       // masked form: key offset c within block blk is valid for this lane's row iff c <= room
+        if (MASKED) {
+            int ln = lane;
+            PIN(ln);
+            int lim = p.Skv - 1;
+            if (CAUSAL) lim = min(lim, q0 + (ln & 31) + off);
+            room = lim - blk * BN - 4 * (ln >> 5);
+        }
         mfma_block(snxt, s0, s2, [&](int slot) __attribute__((always_inline)) {
             // element `slot` of the 32 scores of this lane: exp now, row-sum add one slot later
 #ifdef ABL_NO_EXP
@@ -603,6 +618,10 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
 #else
             ev[slot] = __builtin_amdgcn_exp2f(__builtin_fmaf(scur[slot >> 4][slot & 15], p.c, -m));
 #endif
+            if (MASKED) {
+                const int r = slot & 15;
+                ev[slot] = (32 * (slot >> 4) + 8 * (r >> 2) + (r & 3) <= room) ? ev[slot] : 0.0f;
+            }
             if (slot >= 1) {
                 if ((slot - 1) & 1) { ls1 += ev[slot - 1]; PIN(ls1); } else { ls0 += ev[slot - 1]; PIN(ls0); }
             }
@@ -614,11 +633,13 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
                 PIN(pn[k]);
                 lrn = add_bf16_pair(pn[k], lrn);
             }
-            static_assert(LPT == 2, "request slots below are written out for two loads per tile and wavefront");
-            if (slot == 4) lds_dma16_imm<0>(kp, koff[0], klds);
-            if (slot == 12) lds_dma16_imm<1024>(kp, koff[1], klds);
-            if (slot == 20) lds_dma16_imm<0>(vp, voff[0], vlds);
-            if (slot == 28) lds_dma16_imm<1024>(vp, voff[1], vlds);
+            if (!MASKED) {
+                static_assert(LPT == 2, "request slots below are written out for two loads per tile and wavefront");
+                if (slot == 4) lds_dma16_imm<0>(kp, koff[0], klds);
+                if (slot == 12) lds_dma16_imm<1024>(kp, koff[1], klds);
+                if (slot == 20) lds_dma16_imm<0>(vp, voff[0], vlds);
+                if (slot == 28) lds_dma16_imm<1024>(vp, voff[1], vlds);
+            }
         });
         ls1 += ev[31];
 #pragma unroll
@@ -630,19 +651,27 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
         for (int k = 0; k < 16; ++k) pb[k >> 3][k & 7] = pn[k];
         float ls = ls0 + ls1;
         if (__builtin_amdgcn_ballot_w64(!(ls <= P_SUM_LIMIT)) != 0) {
-            raise_reference(scur);
-            ls = probabilities(scur, lrn);
+            if (MASKED) {
+                softmax_masked(scur, blk);      // adds to l and lr itself
+                ls = 0.0f;
+                lrn = 0.0f;
+            } else {
+                raise_reference(scur);
+                ls = probabilities(scur, lrn);
+            }
         }
         l += ls;
         lr += lrn;
     };
-    // General iteration j: the MFMA block unless block j (and with it every later block) is wholly masked
-    // for this wavefront, then the masked softmax of block j+1 unless that one is wholly masked.
+    auto fast_iteration = [&](f32x16 (&scur)[2], f32x16 (&snxt)[2], int s0, int s1, int s2,
+                              const unsigned char *kp, const unsigned char *vp) __attribute__((always_inline)) {
+        fused_iteration(std::false_type{}, scur, snxt, s0, s1, s2, kp, vp, 0);
+    };
+    // General iteration j, unless block j (and with it every later block) is wholly masked for this
+    // wavefront: the MFMAs of PV(j) and S(j+2) with the masked softmax of S(j+1) between them.
     auto general_iteration = [&](f32x16 (&scur)[2], f32x16 (&snxt)[2], int j) __attribute__((always_inline)) {
         if (j < n_w)
-            mfma_block(snxt, stage_off(j), stage_off(j + 2), [&](int) __attribute__((always_inline)) {});
-        __builtin_amdgcn_sched_barrier(0);
-        if (j + 1 < n_w) softmax_masked(scur, j + 1);
+            fused_iteration(std::true_type{}, scur, snxt, stage_off(j), 0, stage_off(j + 2), nullptr, nullptr, j + 1);
     };
 
     // ---- the workgroup's items, one after the other
