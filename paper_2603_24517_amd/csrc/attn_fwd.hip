@@ -65,11 +65,7 @@ constexpr int LPT = 16 / NWAVES;            // 1 KiB load instructions per tile 
 constexpr int V_BASE = NSTAGE * TILE_BYTES; // K stages first, V stages after them
 constexpr int Q_BASE = 2 * NSTAGE * TILE_BYTES;      // after the stages: Q of the next item, 8 KiB per wavefront
 constexpr int Q_WAVE_BYTES = 32 * ROW_BYTES;
-#ifdef ABL_NO_QSTAGE
-constexpr int LDS_BYTES = Q_BASE;
-#else
 constexpr int LDS_BYTES = Q_BASE + NWAVES * Q_WAVE_BYTES;   // 160 KiB, all of a CU's LDS
-#endif
 // Largest partial row sum (16 probabilities of one lane) the fast softmax path accepts: probabilities
 // stay below 2^14 relative to the reference maximum, far inside BF16 / FP32 range.
 constexpr float P_SUM_LIMIT = 16384.0f;
@@ -500,6 +496,32 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
             __builtin_amdgcn_sched_barrier(0);     // keep the slot order exactly as written
         }
     };
+    // O^T += V^T P^T alone: the last iteration of an item, when no further scores are wanted.
+    auto pv_only = [&](int vb) __attribute__((always_inline)) {
+        constexpr int PREFETCH = MAT_PREFETCH;
+        bf16x8 frag[16];
+        int va[4];
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) va[dt] = vaddr[dt] + vb;
+        auto fetch = [&](int i) __attribute__((always_inline)) -> bf16x8 {
+            const int ro = (i >> 2) * 16 * ROW_BYTES;
+            s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4 *)(lds + va[i & 3] + ro));
+            s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4 *)(lds + va[i & 3] + (ro + 8 * ROW_BYTES)));
+            s16x8 av = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+            return __builtin_bit_cast(bf16x8, av);
+        };
+#pragma unroll
+        for (int i = 0; i < PREFETCH; ++i) frag[i] = fetch(i);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            if (i + PREFETCH < 16) frag[i + PREFETCH] = fetch(i + PREFETCH);
+            const int g = i >> 2;
+            u32x4 pw = {pb[g >> 1][4 * (g & 1)], pb[g >> 1][4 * (g & 1) + 1],
+                        pb[g >> 1][4 * (g & 1) + 2], pb[g >> 1][4 * (g & 1) + 3]};
+            acc[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag[i], __builtin_bit_cast(bf16x8, pw), acc[i & 3], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
     auto rescale = [&](float mn, float alpha) __attribute__((always_inline)) {
         m = mn;
         l *= alpha;
@@ -716,21 +738,14 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
                 __builtin_amdgcn_s_waitcnt(wait_vmcnt(2 * LPT));   // K(0), K(1) landed
                 wg_barrier();
             }
-            // warm: K(0..2), V(0) and this wavefront's Q landed before the last barrier of the item before
-#ifndef ABL_NO_QSTAGE
-            if (warm) {
-#pragma unroll
-                for (int s = 0; s < 8; ++s)
-                    qf[s] = *(const LDS_AS bf16x8 *)(lds + Q_BASE + wave * Q_WAVE_BYTES + kaddr[s]);
-            }
-#endif
+            // warm: K(0), K(1) landed before the last barrier of the item before, and Q is in registers
             qk_only(sa, stage_off(0));
             qk_only(sb, stage_off(1));
             TRACE_MARK(2);
             // P(0): through the masked path, which also handles an empty first block and sets the reference
             softmax_masked(sa, 0);
             TRACE_MARK(3);
-            if (!warm) __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);   // K(2), V(0) landed
+            __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);      // K(2), V(0) landed
             wg_barrier();                                 // and every wavefront is done with K(0), K(1)
             issue_tile(3, false);                         // the requests of "iteration -1"
             issue_tile(1, true);
@@ -791,85 +806,79 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
             }
 #undef ATTN_ADVANCE_REQUESTS
             TRACE_MARK(5);
-            // An item that warms up the next one: its iteration nblk-2 also requests the next Q into this
-            // wavefront's LDS region (after its tile requests, so it may leave those eight loads in
-            // flight too), and its last iteration requests nothing (K'(3) would land in the stage of
-            // K'(0), which is read only after this item's last barrier) and waits for everything.
+            // An item that warms up the next one requests the next Q into this wavefront's LDS region at
+            // the start of its iteration nblk-2 (so that it is older than that iteration's tile requests
+            // and has landed when that iteration ends); its last iteration requests nothing (K'(3) would
+            // land in the stage of K'(0), which is read only after this item's last barrier).
+            auto iteration_start = [&](int jj) __attribute__((always_inline)) {
+                if (warm_next && jj == nblk - 2) request_q(nxt);
+            };
             auto iteration_end = [&](int jj) __attribute__((always_inline)) {
-                if (warm_next && jj >= nblk - 2) {
-                    if (jj == nblk - 2) {
-                        issue_tile(jj + 2 + REQ_AHEAD, false);
-                        issue_tile(jj + REQ_AHEAD, true);
-#ifdef ABL_NO_QSTAGE
-                        __builtin_amdgcn_s_waitcnt(WAIT_ITER_END);
-#else
-                        request_q(nxt);
-                        __builtin_amdgcn_s_waitcnt(wait_vmcnt(2 * LPT + 8));
-#endif
-                    } else {
-                        __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
-                    }
-                } else {
+                if (!(warm_next && jj == nblk - 1)) {
                     issue_tile(jj + 2 + REQ_AHEAD, false);
                     issue_tile(jj + REQ_AHEAD, true);
-                    __builtin_amdgcn_s_waitcnt(WAIT_ITER_END);
                 }
+                __builtin_amdgcn_s_waitcnt(WAIT_ITER_END);
                 wg_barrier();
             };
 #pragma nounroll
-            for (; j < nblk; j += 2) {
+            for (; j < nblk - 1; j += 2) {
+                iteration_start(j);
                 general_iteration(sb, sa, j);
                 iteration_end(j);
-                if (j + 1 < nblk) {
+                if (j + 1 < nblk - 1) {
+                    iteration_start(j + 1);
                     general_iteration(sa, sb, j + 1);
                     iteration_end(j + 1);
                 }
             }
+            // the last iteration has only its PV product left to do
+            if (nblk - 1 < n_w) pv_only(stage_off(nblk - 1));
+            iteration_end(nblk - 1);
             if (!warm_next) __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);   // nothing may still be writing LDS at exit
         }
         TRACE_MARK(6);
 
+        // ---- Q of the next item into registers: from this wavefront's LDS region if it was requested
+        // there (it landed before the last barrier), else straight from memory, behind the epilogue
+        if (warm_next) {
+#pragma unroll
+            for (int s = 0; s < 8; ++s)
+                qf[s] = *(const LDS_AS bf16x8 *)(lds + Q_BASE + wave * Q_WAVE_BYTES + kaddr[s]);
+        } else if (have2) {
+            load_q(nxt);
+        }
         // ---- epilogue: O = acc / lr (BF16), LSE = ln2 * (m + log2 l).  A lane holds one query's values
-        // in pieces of 8 bytes; they go through LDS (two halves of 64 d, 4 KiB per wavefront, in the two
-        // V stages that hold no tile of the next item: those of blocks nblk+1 and nblk+2 of the ring),
-        // so that each store instruction writes whole 128-byte lines.
-#ifdef ABL_NO_QSTAGE
-        if (have2) load_q(nxt);
-#else
-        if (have2 && !warm_next) load_q(nxt);      // not warmed up: straight from memory, behind the epilogue
-#endif
+        // in pieces of 8 bytes; they go through the same LDS region (32 rows of 256 bytes, 16-byte units
+        // swizzled by the row), so that each store instruction writes whole rows.
         const float lt = lane32_sum(l);
         const float lrt = lane32_sum(lr);
         const float inv = lrt > 0.0f ? 1.0f / lrt : 0.0f;
         {
-            const int ob = V_BASE + stage_off(nblk + 1 + (wave >> 2)) + (wave & 3) * 4096;
+            const int ob = Q_BASE + wave * Q_WAVE_BYTES;
             int ln = lane;
             PIN(ln);        // per-lane offsets are formed here, not kept in registers across the block loop
-            const int orow = ln >> 3, ounit = ln & 7, l32 = ln & 31, hh = ln >> 5;
+            const int orow = ln >> 4, ounit = ln & 15, l32 = ln & 31, hh = ln >> 5;
 #pragma unroll
-            for (int half = 0; half < 2; ++half) {
+            for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-                for (int dtl = 0; dtl < 2; ++dtl)
-#pragma unroll
-                    for (int rg = 0; rg < 4; ++rg) {
-                        const int dt = 2 * half + dtl;
-                        u32x2 ww = {pack_bf16(acc[dt][4 * rg] * inv, acc[dt][4 * rg + 1] * inv),
-                                    pack_bf16(acc[dt][4 * rg + 2] * inv, acc[dt][4 * rg + 3] * inv)};
-                        *(LDS_AS u32x2 *)(lds + ob + l32 * 128 + (((4 * dtl + rg) ^ (l32 & 7)) << 4) + 8 * hh) = ww;
-                    }
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int row = 8 * i + orow;
-                    const u32x4 val = *(const LDS_AS u32x4 *)(lds + ob + row * 128 + ((ounit ^ (row & 7)) << 4));
-                    const int qrow = q0 + row;
-                    if (qrow < cold().Sq)
-                        *(u32x4 *)(cold().o + ((size_t)((size_t)b * cold().Sq + qrow) * cold().Hq + head) * HD + 64 * half + 8 * ounit) = val;
+                for (int rg = 0; rg < 4; ++rg) {
+                    u32x2 ww = {pack_bf16(acc[dt][4 * rg] * inv, acc[dt][4 * rg + 1] * inv),
+                                pack_bf16(acc[dt][4 * rg + 2] * inv, acc[dt][4 * rg + 3] * inv)};
+                    *(LDS_AS u32x2 *)(lds + ob + l32 * ROW_BYTES + (((4 * dt + rg) ^ (l32 & 15)) << 4) + 8 * hh) = ww;
                 }
+            const size_t o_row_bytes = (size_t)cold().Hq * HD * 2;
+            unsigned char *og = (unsigned char *)(cold().o + ((size_t)((size_t)b * cold().Sq + q0) * cold().Hq + head) * HD);
+            const int rows = cold().Sq - q0;        // rows of this wavefront that exist
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int row = 4 * i + orow;
+                const u32x4 val = *(const LDS_AS u32x4 *)(lds + ob + row * ROW_BYTES + ((ounit ^ (row & 15)) << 4));
+                if (row < rows) *(u32x4 *)(og + row * o_row_bytes + 16 * ounit) = val;
             }
-            const int qrow = q0 + l32;
-            if (qrow < cold().Sq && hh == 0) {
+            if (l32 < rows && hh == 0) {
                 const float lse = lt > 0.0f ? (m + __builtin_amdgcn_logf(lt)) * 0.6931471805599453f : -INFINITY;
-                cold().lse[((size_t)b * cold().Hq + head) * cold().Sq + qrow] = lse;
+                cold().lse[((size_t)b * cold().Hq + head) * cold().Sq + q0 + l32] = lse;
             }
         }
         TRACE_MARK(7);
