@@ -785,25 +785,46 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
                 kp += step;                                                                  \
                 --kleft;                                                                     \
             } while (0)
-            int s0 = stage_off(0), s1 = stage_off(1), s2 = stage_off(2);
+#define ATTN_FAST(scur, snxt, a0, a1, a2)                                                    \
+            do {                                                                             \
+                fast_iteration(scur, snxt, a0, a1, a2, kp, vp);                              \
+                ATTN_ADVANCE_REQUESTS();                                                     \
+                TRACE_WAIT_BEGIN();                                                          \
+                __builtin_amdgcn_s_waitcnt(WAIT_ITER_END);                                   \
+                TRACE_WAIT_MID();                                                            \
+                wg_barrier();                                                                \
+                TRACE_WAIT_END();                                                            \
+            } while (0)
+            // The bulk of the fast iterations runs in a loop unrolled six times (two score buffers x three
+            // stages), in which every LDS address is a register plus a constant.  That loop wants block j in
+            // stage 0; a two-iteration loop with the stages in registers brings j there, and takes what
+            // is left afterwards.
+            static_assert(NSTAGE == 3, "the unrolled loop below is written for three stages");
+            const int j_align = ring0 == 0 ? 0 : 2 * ring0 == 2 ? 2 : 4;     // smallest even j with (ring0 + j) % 3 == 0
 #pragma nounroll
-            for (; j + 1 < fast_end; j += 2) {
-                fast_iteration(sb, sa, s0, s1, s2, kp, vp);
-                ATTN_ADVANCE_REQUESTS();
-                TRACE_WAIT_BEGIN();
-                __builtin_amdgcn_s_waitcnt(WAIT_ITER_END);
-                TRACE_WAIT_MID();
-                wg_barrier();
-                TRACE_WAIT_END();
-                fast_iteration(sa, sb, s1, s2, s0, kp, vp);
-                ATTN_ADVANCE_REQUESTS();
-                { const int t = s0; s0 = s2; s2 = s1; s1 = t; }
-                TRACE_WAIT_BEGIN();
-                __builtin_amdgcn_s_waitcnt(WAIT_ITER_END);
-                TRACE_WAIT_MID();
-                wg_barrier();
-                TRACE_WAIT_END();
+            for (int round = 0; round < 2; ++round) {
+                const int lim = round == 0 ? min(fast_end, j_align) : fast_end;
+                int s0 = stage_off(j), s1 = stage_off(j + 1), s2 = stage_off(j + 2);
+#pragma nounroll
+                for (; j + 1 < lim; j += 2) {
+                    ATTN_FAST(sb, sa, s0, s1, s2);
+                    ATTN_FAST(sa, sb, s1, s2, s0);
+                    { const int t = s0; s0 = s2; s2 = s1; s1 = t; }
+                }
+                if (round == 0) {
+                    constexpr int T0 = 0, T1 = TILE_BYTES, T2 = 2 * TILE_BYTES;
+#pragma nounroll
+                    for (; j + 5 < fast_end; j += 6) {
+                        ATTN_FAST(sb, sa, T0, T1, T2);
+                        ATTN_FAST(sa, sb, T1, T2, T0);
+                        ATTN_FAST(sb, sa, T2, T0, T1);
+                        ATTN_FAST(sa, sb, T0, T1, T2);
+                        ATTN_FAST(sb, sa, T1, T2, T0);
+                        ATTN_FAST(sa, sb, T2, T0, T1);
+                    }
+                }
             }
+#undef ATTN_FAST
 #undef ATTN_ADVANCE_REQUESTS
             TRACE_MARK(5);
             // An item that warms up the next one requests the next Q into this wavefront's LDS region at
