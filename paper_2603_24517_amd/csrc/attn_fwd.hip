@@ -77,25 +77,59 @@ constexpr int WAIT_VMCNT0 = wait_vmcnt(0);
 // end of an iteration: everything but the loads of the last REQ_AHEAD-1 iterations has landed
 constexpr int WAIT_ITER_END = wait_vmcnt((REQ_AHEAD - 1) * 2 * LPT);
 
-struct Params {
-    const __bf16 *q, *k, *v;
-    __bf16 *o;
-    float *lse;
-    int B, Hq, Hkv, Sq, Skv;
-    int G;          // Hq / Hkv
-    int pack;       // query heads of one K/V group served by one workgroup (a power of two <= NWAVES)
-    int tile_pos;   // query positions per workgroup = WG_ROWS / pack
-    int ntile;      // ceil(Sq / tile_pos)
-    int chunks;     // G / pack
+// Exact n / d for 0 <= n < 2^31 as a multiply-high, an add and a shift; the constants come from the host.
+struct Div { uint32_t mul, shift; };
+__host__ __device__ inline uint32_t fast_div(uint32_t n, const Div d) {
+#ifdef __HIP_DEVICE_COMPILE__
+    return (__umulhi(n, d.mul) + n) >> d.shift;
+#else
+    return (uint32_t)((((uint64_t)n * d.mul) >> 32) + n) >> d.shift;
+#endif
+}
+inline Div make_div(uint32_t d) {
+    Div r;
+    r.shift = 0;
+    while ((1u << r.shift) < d) ++r.shift;
+    r.mul = (uint32_t)((((uint64_t)1 << 32) * (((uint64_t)1 << r.shift) - d)) / d + 1);
+    return r;
+}
+
+// How the work items are dealt out (read by the per-item code only).
+struct Sched {
     int total;      // work items = B * Hkv * chunks * ntile
     int per_xcd;    // entries in the work list of one XCD (non-causal: ceil(total / 8))
     int slots;      // workgroups per XCD in this launch (one per CU); the grid is 8 * slots
+    int ntile;      // ceil(Sq / tile_pos)
     // causal only: how the (group, tile) pairs are dealt to the XCDs (a group = one batch entry, K/V head and chunk)
-    int split;      // every group is cut into `split` sub-groups, sub-group r holding the tiles t = r (mod split)
+    int split;      // every group is cut into `split` sub-groups (a power of two), sub-group r holding the tiles t = r (mod split)
+    int split_log2;
     int nsub;       // tiles per sub-group = ceil(ntile / split); the padding entries are skipped
     int sgx;        // sub-groups per XCD = groups * split / 8
     int window;     // sub-groups that one XCD works through together, longest tiles of all of them first
+    int per_win;    // window * nsub
+    Div d_ntile, d_per_win, d_window;
+};
+// Tensor shape and head packing (read by the per-item code only).
+struct Shape {
+    int Sq, Hq;
+    int G;          // Hq / Hkv
+    int pack;       // query heads of one K/V group served by one workgroup (a power of two <= NWAVES)
+    int pack_log2;
+    int tile_pos;   // query positions per workgroup = WG_ROWS / pack
+    int chunks;     // G / pack
+    Div d_chunks, d_hkv;
+};
+struct Params {
+    const __bf16 *k, *v;
+    int Hkv, Skv;
     float c;        // scale * log2(e)
+    int pad_;
+    // the rest is read from the argument block where it is needed
+    const __bf16 *q;
+    __bf16 *o;
+    float *lse;
+    Shape shape;
+    Sched sched;
 };
 
 __device__ __forceinline__ float lane32_max(float x) {
@@ -216,34 +250,45 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31;
     const int hh = lane >> 5;
-    const int off = p.Skv - p.Sq;                               // causal: key j valid iff j <= i + off
+    const int off = p.Skv - cold().shape.Sq;                    // causal: key j valid iff j <= i + off
     const int nfull = p.Skv / BN;                               // tiles below this index are full
     const bool all_full = (p.Skv % BN) == 0;
 
+    // one wide scalar load each, where the per-item code starts
+    auto load_sched = [&]() __attribute__((always_inline)) -> Sched {
+        Sched sc;
+        __builtin_memcpy(&sc, &cold().sched, sizeof(Sched));
+        return sc;
+    };
+    auto load_shape = [&]() __attribute__((always_inline)) -> Shape {
+        Shape sh;
+        __builtin_memcpy(&sh, &cold().shape, sizeof(Shape));
+        return sh;
+    };
     // entry j of this XCD's list -> (group, tile); false for a padding entry
-    auto decode = [&](int j, int &grp, int &tile) __attribute__((always_inline)) -> bool {
+    auto decode = [&](const Sched &sc, int j, int &grp, int &tile) __attribute__((always_inline)) -> bool {
         if (CAUSAL) {
-            const int per_win = cold().window * cold().nsub;
-            const int w = j / per_win;
-            const int r = j - w * per_win;
-            const int kw = min(cold().window, cold().sgx - w * cold().window);     // the last window may be narrower
-            const int st = r / kw;
-            const int sg = xcd * cold().sgx + w * cold().window + (r - st * kw);
-            grp = sg / cold().split;
-            const int tile_r = st * cold().split + (sg - grp * cold().split);
-            tile = cold().ntile - 1 - tile_r;                            // long (late) query tiles first
-            return tile_r < cold().ntile;
+            const int w = fast_div(j, sc.d_per_win);
+            const int r = j - w * sc.per_win;
+            const int kw = min(sc.window, sc.sgx - w * sc.window);      // the last window may be narrower
+            const int st = kw == sc.window ? (int)fast_div(r, sc.d_window) : r / kw;
+            const int sg = xcd * sc.sgx + w * sc.window + (r - st * kw);
+            grp = sg >> sc.split_log2;
+            const int tile_r = st * sc.split + (sg & (sc.split - 1));
+            tile = sc.ntile - 1 - tile_r;                               // long (late) query tiles first
+            return tile_r < sc.ntile;
         }
-        const int item = xcd * cold().per_xcd + j;
-        tile = item % cold().ntile;
-        grp = item / cold().ntile;
-        return item < cold().total;
+        const int item = xcd * sc.per_xcd + j;
+        grp = fast_div(item, sc.d_ntile);
+        tile = item - grp * sc.ntile;
+        return item < sc.total;
     };
     // first round >= r in which this workgroup has a real entry; false when its list is exhausted
     auto find_item = [&](int &r, int &grp, int &tile) __attribute__((always_inline)) -> bool {
-        for (; r * cold().slots < cold().per_xcd; ++r) {
-            const int j = r * cold().slots + ((CAUSAL && (r & 1)) ? cold().slots - 1 - slot : slot);
-            if (j < cold().per_xcd && decode(j, grp, tile)) return true;
+        const Sched sc = load_sched();
+        for (; r * sc.slots < sc.per_xcd; ++r) {
+            const int j = r * sc.slots + ((CAUSAL && (r & 1)) ? sc.slots - 1 - slot : slot);
+            if (j < sc.per_xcd && decode(sc, j, grp, tile)) return true;
         }
         return false;
     };
@@ -256,16 +301,17 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
     const size_t kv_row_bytes = (size_t)p.Hkv * HD * 2;
     const size_t tile_gbytes = (size_t)BN * kv_row_bytes;
     auto geometry = [&](int grp, int tile) __attribute__((always_inline)) -> Geo {
+        const Shape sh = load_shape();
         Geo g;
-        const int chunk = grp % cold().chunks;
-        const int bh = grp / cold().chunks;
-        const int hkv = bh % p.Hkv;
-        g.b = bh / p.Hkv;
-        g.head = hkv * cold().G + chunk * cold().pack + (wave % cold().pack);
-        g.q0 = tile * cold().tile_pos + (wave / cold().pack) * 32;
+        const int bh = fast_div(grp, sh.d_chunks);
+        const int chunk = grp - bh * sh.chunks;
+        g.b = fast_div(bh, sh.d_hkv);
+        const int hkv = bh - g.b * p.Hkv;
+        g.head = hkv * sh.G + chunk * sh.pack + (wave & (sh.pack - 1));
+        g.q0 = tile * sh.tile_pos + (wave >> sh.pack_log2) * 32;
         g.nblk = (p.Skv + BN - 1) / BN;
         if (CAUSAL) {
-            const int klast = min(tile * cold().tile_pos + cold().tile_pos, cold().Sq) - 1 + off;
+            const int klast = min(tile * sh.tile_pos + sh.tile_pos, sh.Sq) - 1 + off;
             g.nblk = klast < 0 ? 0 : min(g.nblk, klast / BN + 1);
         }
         g.kg = (const unsigned char *)(p.k + ((size_t)g.b * p.Skv * p.Hkv + hkv) * HD);
@@ -316,18 +362,20 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
                            // normalised by this one, so that a rounding error in a dominant weight
                            // cancels between numerator and denominator
     auto load_q = [&](const Geo &g) __attribute__((always_inline)) {
-        const int qrow = min(g.q0 + l32, cold().Sq - 1);
-        const __bf16 *qp = cold().q + ((size_t)((size_t)g.b * cold().Sq + qrow) * cold().Hq + g.head) * HD + 8 * hh;
+        const int Sq = cold().shape.Sq, Hq = cold().shape.Hq;
+        const int qrow = min(g.q0 + l32, Sq - 1);
+        const __bf16 *qp = cold().q + ((size_t)((size_t)g.b * Sq + qrow) * Hq + g.head) * HD + 8 * hh;
 #pragma unroll
         for (int s = 0; s < 8; ++s) qf[s] = *(const bf16x8 *)(qp + 16 * s);
     };
     // The same through LDS: requested (wave-private region, the K swizzle) while the item before is
     // still in its last iterations, fetched into registers when the item starts.
     auto request_q = [&](const Geo &g) __attribute__((always_inline)) {
-        const size_t q_row_bytes = (size_t)cold().Hq * HD * 2;
-        const int q0c = min(g.q0, cold().Sq - 1);       // rows past the end of Q re-read the last row
-        const unsigned char *qg = (const unsigned char *)(cold().q + ((size_t)((size_t)g.b * cold().Sq + q0c) * cold().Hq + g.head) * HD);
-        const int last = cold().Sq - 1 - q0c;
+        const int Sq = cold().shape.Sq, Hq = cold().shape.Hq;
+        const size_t q_row_bytes = (size_t)Hq * HD * 2;
+        const int q0c = min(g.q0, Sq - 1);          // rows past the end of Q re-read the last row
+        const unsigned char *qg = (const unsigned char *)(cold().q + ((size_t)((size_t)g.b * Sq + q0c) * Hq + g.head) * HD);
+        const int last = Sq - 1 - q0c;
         const uint32_t lbase = (uint32_t)(uintptr_t)lds + Q_BASE + wave * Q_WAVE_BYTES;
         int ln = lane;
         PIN(ln);            // per-lane offsets are formed here, not kept in registers across the block loop
@@ -888,9 +936,10 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
                                 pack_bf16(acc[dt][4 * rg + 2] * inv, acc[dt][4 * rg + 3] * inv)};
                     *(LDS_AS u32x2 *)(lds + ob + l32 * ROW_BYTES + (((4 * dt + rg) ^ (l32 & 15)) << 4) + 8 * hh) = ww;
                 }
-            const size_t o_row_bytes = (size_t)cold().Hq * HD * 2;
-            unsigned char *og = (unsigned char *)(cold().o + ((size_t)((size_t)b * cold().Sq + q0) * cold().Hq + head) * HD);
-            const int rows = cold().Sq - q0;        // rows of this wavefront that exist
+            const int Sq = cold().shape.Sq, Hq = cold().shape.Hq;
+            const size_t o_row_bytes = (size_t)Hq * HD * 2;
+            unsigned char *og = (unsigned char *)(cold().o + ((size_t)((size_t)b * Sq + q0) * Hq + head) * HD);
+            const int rows = Sq - q0;               // rows of this wavefront that exist
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 const int row = 4 * i + orow;
@@ -899,7 +948,7 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
             }
             if (l32 < rows && hh == 0) {
                 const float lse = lt > 0.0f ? (m + __builtin_amdgcn_logf(lt)) * 0.6931471805599453f : -INFINITY;
-                cold().lse[((size_t)b * cold().Hq + head) * cold().Sq + q0 + l32] = lse;
+                cold().lse[((size_t)b * Hq + head) * Sq + q0 + l32] = lse;
             }
         }
         TRACE_MARK(7);
@@ -962,23 +1011,29 @@ int attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
     if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o) & 15) return ATTN_E_ALIGN;
     if ((uintptr_t)lse & 3) return ATTN_E_ALIGN;
 
-    Params p;
+    Params p = {};
     p.q = (const __bf16 *)q; p.k = (const __bf16 *)k; p.v = (const __bf16 *)v;
     p.o = (__bf16 *)o; p.lse = lse;
-    p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.Sq = Sq; p.Skv = Skv;
-    p.G = Hq / Hkv;
-    p.pack = (NWAVES >= 8 && p.G % 8 == 0) ? 8 : (p.G % 4 == 0) ? 4 : (p.G % 2 == 0) ? 2 : 1;
-    p.tile_pos = WG_ROWS / p.pack;
-    p.ntile = (Sq + p.tile_pos - 1) / p.tile_pos;
-    p.chunks = p.G / p.pack;
-    // Key/query indices and the work-item count are 32-bit in the kernel.
-    if ((int64_t)Sq + Skv + WG_ROWS + 8 * BN >= INT32_MAX) return ATTN_E_UNSUPPORTED;
-    const int64_t total = (int64_t)B * Hkv * p.chunks * p.ntile;
-    if (total + 8 >= INT32_MAX) return ATTN_E_UNSUPPORTED;
-    p.total = (int)total;
+    p.Hkv = Hkv; p.Skv = Skv;
     p.c = scale * 1.4426950408889634f;
+    Shape &sh = p.shape;
+    Sched &sc = p.sched;
+    sh.Sq = Sq; sh.Hq = Hq;
+    sh.G = Hq / Hkv;
+    sh.pack = (sh.G % 8 == 0) ? 8 : (sh.G % 4 == 0) ? 4 : (sh.G % 2 == 0) ? 2 : 1;
+    sh.pack_log2 = sh.pack == 8 ? 3 : sh.pack == 4 ? 2 : sh.pack == 2 ? 1 : 0;
+    sh.tile_pos = WG_ROWS / sh.pack;
+    sh.chunks = sh.G / sh.pack;
+    sh.d_chunks = make_div((uint32_t)sh.chunks);
+    sh.d_hkv = make_div((uint32_t)Hkv);
+    sc.ntile = (Sq + sh.tile_pos - 1) / sh.tile_pos;
+    // Key/query indices and the work-item count are 32-bit in the kernel (and below 2^31 for the divisions).
+    if ((int64_t)Sq + Skv + WG_ROWS + 8 * BN >= INT32_MAX) return ATTN_E_UNSUPPORTED;
+    const int64_t total = (int64_t)B * Hkv * sh.chunks * sc.ntile;
+    if (total + 8 >= INT32_MAX / 16) return ATTN_E_UNSUPPORTED;
+    sc.total = (int)total;
 
-    // Once per device: the CU count, and the opt-in that 96 KiB of dynamic LDS needs.
+    // Once per device: the CU count, and the opt-in that 160 KiB of dynamic LDS needs.
     static int cus[64] = {};
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return ATTN_E_LAUNCH;
@@ -992,22 +1047,25 @@ int attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
             return ATTN_E_LAUNCH;
         cus[dev] = n;
     }
-    // One workgroup per CU (a workgroup takes all of a CU's registers), each working through a list.
+    // One workgroup per CU (a workgroup takes all of a CU's registers and LDS), each working through a list.
     const int cu_slots = cus[dev] >= 8 ? cus[dev] / 8 : 1;
-    p.per_xcd = (int)((total + 7) / 8);
-    p.split = p.nsub = p.sgx = p.window = 1;
+    sc.per_xcd = (int)((total + 7) / 8);
+    sc.split = sc.nsub = sc.sgx = sc.window = 1;
+    sc.split_log2 = 0;
     if (causal) {
-        const int64_t groups = (int64_t)B * Hkv * p.chunks;
-        while ((groups * p.split) % 8 != 0) p.split *= 2;               // 1, 2, 4 or 8
-        p.nsub = (p.ntile + p.split - 1) / p.split;
-        p.sgx = (int)(groups * p.split / 8);
-        while (p.window * 2 <= p.sgx && p.window * p.nsub < cu_slots) p.window *= 2;
-        const int64_t entries = (int64_t)p.sgx * p.nsub;
-        if (entries * 8 + 8 >= INT32_MAX) return ATTN_E_UNSUPPORTED;
-        p.per_xcd = (int)entries;
+        const int64_t groups = (int64_t)B * Hkv * sh.chunks;
+        while ((groups * sc.split) % 8 != 0) { sc.split *= 2; ++sc.split_log2; }    // 1, 2, 4 or 8
+        sc.nsub = (sc.ntile + sc.split - 1) / sc.split;
+        sc.sgx = (int)(groups * sc.split / 8);
+        while (sc.window * 2 <= sc.sgx && sc.window * sc.nsub < cu_slots) sc.window *= 2;
+        sc.per_xcd = sc.sgx * sc.nsub;          // <= total + padding, far below 2^31 after the check above
     }
-    p.slots = p.per_xcd < cu_slots ? p.per_xcd : cu_slots;
-    const dim3 grid((unsigned)(p.slots * 8)), block(NTHREADS);
+    sc.per_win = sc.window * sc.nsub;
+    sc.d_ntile = make_div((uint32_t)sc.ntile);
+    sc.d_per_win = make_div((uint32_t)sc.per_win);
+    sc.d_window = make_div((uint32_t)sc.window);
+    sc.slots = sc.per_xcd < cu_slots ? sc.per_xcd : cu_slots;
+    const dim3 grid((unsigned)(sc.slots * 8)), block(NTHREADS);
     hipStream_t st = (hipStream_t)stream;
     if (causal)
         hipLaunchKernelGGL(attn_fwd_kernel<true>, grid, block, LDS_BYTES, st, p);
