@@ -32,6 +32,17 @@
 // reads, a few VALU), so the matrix pipe and the vector ALU run at the same
 // time (the paper's section 2.2 describes the same need, met on its hardware
 // by specialised warps), with one workgroup barrier per iteration.
+//
+// The launch has one workgroup per CU, and each works through a list of
+// (batch entry, K/V head, query tile) items: while an item is in its last
+// blocks it already requests the next item's first K/V tiles into the stages
+// that fall free and the next item's Q into the rest of LDS, and O leaves
+// through LDS as whole rows, so that the matrix pipe idles for little more
+// than one short prologue per item.  The per-iteration overhead of the loop
+// (stage rotation, request addresses, LDS address arithmetic) is kept out of
+// the instruction stream as far as possible, because with two wavefronts per
+// SIMD the issue of vector instructions, not the matrix pipe alone, is what
+// an iteration's length follows.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <math.h>
@@ -113,7 +124,7 @@ struct Sched {
 struct Shape {
     int Sq, Hq;
     int G;          // Hq / Hkv
-    int pack;       // query heads of one K/V group served by one workgroup (a power of two <= NWAVES)
+    int pack;       // query heads of one K/V group served by one workgroup (1, 2, 4 or 8)
     int pack_log2;
     int tile_pos;   // query positions per workgroup = WG_ROWS / pack
     int chunks;     // G / pack
@@ -165,9 +176,6 @@ __device__ __forceinline__ const unsigned char *uniform_ptr(const unsigned char 
     return (const unsigned char *)(uintptr_t)(((uint64_t)hi << 32) | lo);
 }
 __device__ __forceinline__ void lds_dma16(const unsigned char *base, uint32_t voffset, uint32_t lds_base) {
-#ifdef ABL_NO_DMA
-    return;
-#endif
     base = uniform_ptr(base);
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
@@ -177,9 +185,6 @@ __device__ __forceinline__ void lds_dma16(const unsigned char *base, uint32_t vo
 // The same with the LDS address given as a scalar plus a compile-time constant (one scalar instruction).
 template <int IMM>
 __device__ __forceinline__ void lds_dma16_imm(const unsigned char *base, uint32_t voffset, uint32_t lds_base) {
-#ifdef ABL_NO_DMA
-    return;
-#endif
     asm volatile("s_add_u32 m0, %0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
                  : "s"(lds_base), "v"(voffset), "s"(base), "n"(IMM)
@@ -188,9 +193,6 @@ __device__ __forceinline__ void lds_dma16_imm(const unsigned char *base, uint32_
 // Keeps the instruction that produces x at this point of the program order (no code is emitted).
 #define PIN(x) asm volatile("" : "+v"(x))
 __device__ __forceinline__ void wg_barrier() {
-#ifdef ABL_NO_BARRIER
-    return;
-#endif
     __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
@@ -413,15 +415,8 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
     const uint32_t lds_wave = (uint32_t)(uintptr_t)lds + wave * (LPT * 1024);
     // The three stages are a ring that runs on from one item to the next: block j of the item in work
     // lives in stage (ring0 + j) % 3, and blocks nblk, nblk+1, ... are blocks 0, 1, ... of the next item.
-#ifdef ABL_ONE_STAGE
-    auto stage_off = [&](int) __attribute__((always_inline)) { return 0; };
-#else
     auto stage_off = [&](int blk) __attribute__((always_inline)) { return ((blk + ring0) % NSTAGE) * TILE_BYTES; };
-#endif
     auto next_stage = [&](int o) __attribute__((always_inline)) {      // stage_off(blk + 1) from stage_off(blk)
-#ifdef ABL_ONE_STAGE
-        return o;
-#endif
         return o == (NSTAGE - 1) * TILE_BYTES ? 0 : o + TILE_BYTES;
     };
     // Global address of the tile that request `blk_req` stands for: a block of this item, or (past its
@@ -683,11 +678,7 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
         }
         mfma_block(snxt, s0, s2, [&](int slot) __attribute__((always_inline)) {
             // element `slot` of the 32 scores of this lane: exp now, row-sum add one slot later
-#ifdef ABL_NO_EXP
-            ev[slot] = __builtin_fmaf(scur[slot >> 4][slot & 15], p.c, -m);
-#else
             ev[slot] = __builtin_amdgcn_exp2f(__builtin_fmaf(scur[slot >> 4][slot & 15], p.c, -m));
-#endif
             if (MASKED) {
                 const int r = slot & 15;
                 ev[slot] = (32 * (slot >> 4) + 8 * (r >> 2) + (r & 3) <= room) ? ev[slot] : 0.0f;
