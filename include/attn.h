@@ -51,6 +51,12 @@ enum {
  *   scale   finite and >= 0 (the caller passes 1/sqrt(D))
  *   stream  a hipStream_t, or NULL for the default stream
  *
+ * Size limits (ATTN_E_UNSUPPORTED beyond them): Sq + Skv below 2^31 - 1024,
+ * and fewer than 2^27 work items, one item being 256/p query rows of p query
+ * heads that share a K/V head (p = 8, 4, 2 or 1, the largest that divides
+ * Hq / Hkv).  The launch uses one workgroup per compute unit of the current
+ * device (all of its LDS); the first call on a device queries the device once.
+ *
  * Inputs and outputs must not overlap and must stay alive until the stream
  * reaches the end of the kernel.  The call only enqueues work.  Every
  * argument is checked on the host before the device is touched; the return
