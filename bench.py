@@ -65,19 +65,29 @@ def traffic_from_profiles(name):
 
 
 def cpu_baseline(w, q, k, v, o_gpu, lse_gpu, budget_s=12.0):
-    """Time the FP64 oracle (as it stands) on a bounded row sample and check the GPU output on it."""
+    """Time the FP64 oracle (as it stands) on a bounded row sample and check the GPU output on it.
+
+    The stratified sample is worked through in chunks of growing size until about budget_s seconds of
+    oracle time have been spent (or the sample is exhausted); the first, small chunk only warms up the
+    oracle's threads and is not timed."""
     import oracle
     rows_all = W.sample_rows(w, 393216)
+    rows_all = rows_all[np.random.default_rng(w.seed).permutation(len(rows_all))]   # any prefix is a stratified sample
     qd, kd, vd = q.double().numpy(), k.double().numpy(), v.double().numpy()
-    pilot = rows_all[:: max(1, len(rows_all) // 256)][:256]
-    t0 = time.perf_counter()
-    oracle.attn_ref_rows(qd, kd, vd, pilot, w.causal, w.scale)
-    dt = max(time.perf_counter() - t0, 1e-4)
-    n = int(min(len(rows_all), max(256, budget_s / dt * len(pilot))))   # about budget_s seconds of oracle work
-    rows = rows_all[:: max(1, len(rows_all) // n)][:n]
-    t0 = time.perf_counter()
-    o_ref, lse_ref = oracle.attn_ref_rows(qd, kd, vd, rows, w.causal, w.scale)
-    dt = time.perf_counter() - t0
+    oracle.attn_ref_rows(qd, kd, vd, rows_all[:64], w.causal, w.scale)
+    done, chunk, dt = 0, 1024, 0.0
+    o_parts, l_parts = [], []
+    while done < len(rows_all) and dt < budget_s:
+        rows = rows_all[done:done + chunk]
+        t0 = time.perf_counter()
+        o_ref, lse_ref = oracle.attn_ref_rows(qd, kd, vd, rows, w.causal, w.scale)
+        dt += time.perf_counter() - t0
+        o_parts.append(o_ref)
+        l_parts.append(lse_ref)
+        done += len(rows)
+        chunk *= 2
+    rows = rows_all[:done]
+    o_ref, lse_ref = np.concatenate(o_parts), np.concatenate(l_parts)
     i = rows[:, 2].astype(np.int64)
     nvalid = np.minimum(w.Skv, i + 1 + w.Skv - w.Sq) if w.causal else np.full_like(i, w.Skv)
     flops = 4.0 * float(nvalid.clip(min=0).sum()) * w.D          # work the oracle really did
