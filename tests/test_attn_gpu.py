@@ -217,6 +217,9 @@ MANY_ITEMS = [
     (4, 64, 64, 960, 960),     # four rounds, every tile full
     (3, 5, 5, 5000, 5000),     # 15 heads: causal tiles split eight ways over the XCDs
     (2, 6, 2, 4100, 4100),     # 4 groups after packing 3 heads singly: split two ways
+    (64, 64, 64, 256, 256),    # 4096 items of exactly four blocks: the shortest item that carries the next one's requests
+    (32, 16, 2, 320, 320),     # group of 8 packed, ten tiles of 32 positions, five blocks
+    (1, 48, 6, 1111, 1111),    # group of 8 in one chunk, ragged everywhere, six K/V heads
 ]
 
 
