@@ -416,9 +416,6 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
     // The three stages are a ring that runs on from one item to the next: block j of the item in work
     // lives in stage (ring0 + j) % 3, and blocks nblk, nblk+1, ... are blocks 0, 1, ... of the next item.
     auto stage_off = [&](int blk) __attribute__((always_inline)) { return ((blk + ring0) % NSTAGE) * TILE_BYTES; };
-    auto next_stage = [&](int o) __attribute__((always_inline)) {      // stage_off(blk + 1) from stage_off(blk)
-        return o == (NSTAGE - 1) * TILE_BYTES ? 0 : o + TILE_BYTES;
-    };
     // Global address of the tile that request `blk_req` stands for: a block of this item, or (past its
     // end) a block of the next item if that one is being warmed up; otherwise, and past the end of
     // the next item too, the last block is read again into the (dead) stage the request would have
