@@ -370,8 +370,8 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
 #pragma unroll
         for (int s = 0; s < 8; ++s) qf[s] = *(const bf16x8 *)(qp + 16 * s);
     };
-    // The same through LDS: requested (wave-private region, the K swizzle) while the item before is
-    // still in its last iterations, fetched into registers when the item starts.
+    // The same through LDS: requested (wave-private region, the K swizzle) when the item before
+    // starts, fetched into registers when that one's last block is done.
     auto request_q = [&](const Geo &g) __attribute__((always_inline)) {
         const int Sq = cold().shape.Sq, Hq = cold().shape.Hq;
         const size_t q_row_bytes = (size_t)Hq * HD * 2;
@@ -758,6 +758,10 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
         // iterations j >= nblk-4), which takes four iterations to host them.
         warm_next = have2 && nblk >= 2 + REQ_AHEAD && nxt.nblk > 0;
         nx_nblk = nxt.nblk; nx_kg = nxt.kg; nx_vg = nxt.vg;
+        // Its Q goes into this wavefront's LDS region now (the epilogue of the item before is done with
+        // it) and into registers when this item's last block is done; being the oldest request of the
+        // item, it never holds up a wait for tiles.
+        if (have2) request_q(nxt);
 
         TRACE_MARK(1);
         if (nblk > 0) {
@@ -781,7 +785,9 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
             // P(0): through the masked path, which also handles an empty first block and sets the reference
             softmax_masked(sa, 0);
             TRACE_MARK(3);
-            __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);      // K(2), V(0) landed
+            // K(2), V(0) landed: a warm item waited for them before the epilogue of the item before, and
+            // what it still has in flight are that epilogue's stores, which nothing here depends on
+            if (!warm) __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
             wg_barrier();                                 // and every wavefront is done with K(0), K(1)
             issue_tile(3, false);                         // the requests of "iteration -1"
             issue_tile(1, true);
@@ -796,8 +802,6 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
             // Iterations j < fast_end take the fast path: S(j+1) needs no mask, and the tiles requested are
             // full ones (past the last block: of the next item, or the last block again).
             int fast_end = all_full ? n_unm - 1 : min(n_unm - 1, nfull - (2 + REQ_AHEAD));
-            // the last two iterations of an item that warms up the next one have extra duties (below)
-            if (warm_next) fast_end = min(fast_end, nblk - 2);
             // Request addresses of the fast loop.  K and V have the same shape, so V's address is K's of
             // two iterations earlier plus the distance between the tensors; K's moves on by one tile per
             // iteration, except at the item's last block (on to block 0 of the next item, or stay) and,
@@ -860,16 +864,16 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
                     }
                 }
             }
+            // an item without masks whose last fast iteration is left over by the loops of two
+            if (j == nblk - 2 && fast_end == nblk - 1) {
+                ATTN_FAST(sb, sa, stage_off(j), stage_off(j + 1), stage_off(j + 2));
+                ++j;
+            }
 #undef ATTN_FAST
 #undef ATTN_ADVANCE_REQUESTS
             TRACE_MARK(5);
-            // An item that warms up the next one requests the next Q into this wavefront's LDS region at
-            // the start of its iteration nblk-2 (so that it is older than that iteration's tile requests
-            // and has landed when that iteration ends); its last iteration requests nothing (K'(3) would
+            // The last iteration of an item that warms up the next one requests nothing (K'(3) would
             // land in the stage of K'(0), which is read only after this item's last barrier).
-            auto iteration_start = [&](int jj) __attribute__((always_inline)) {
-                if (warm_next && jj == nblk - 2) request_q(nxt);
-            };
             auto iteration_end = [&](int jj) __attribute__((always_inline)) {
                 if (!(warm_next && jj == nblk - 1)) {
                     issue_tile(jj + 2 + REQ_AHEAD, false);
@@ -880,11 +884,9 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
             };
 #pragma nounroll
             for (; j < nblk - 1; j += 2) {
-                iteration_start(j);
                 general_iteration(sb, sa, j);
                 iteration_end(j);
                 if (j + 1 < nblk - 1) {
-                    iteration_start(j + 1);
                     general_iteration(sa, sb, j + 1);
                     iteration_end(j + 1);
                 }
@@ -892,18 +894,18 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
             // the last iteration has only its PV product left to do
             if (nblk - 1 < n_w) pv_only(stage_off(nblk - 1));
             iteration_end(nblk - 1);
-            if (!warm_next) __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);   // nothing may still be writing LDS at exit
         }
+        // Nothing may still be writing LDS at exit; the next item's Q has landed; and its K'(2), V'(0) are
+        // waited for here, before the epilogue's stores join the queue, so that its first barrier can
+        // publish them.
+        __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
         TRACE_MARK(6);
 
-        // ---- Q of the next item into registers: from this wavefront's LDS region if it was requested
-        // there (it landed before the last barrier), else straight from memory, behind the epilogue
-        if (warm_next) {
+        // ---- Q of the next item into registers, from this wavefront's LDS region
+        if (have2) {
 #pragma unroll
             for (int s = 0; s < 8; ++s)
                 qf[s] = *(const LDS_AS bf16x8 *)(lds + Q_BASE + wave * Q_WAVE_BYTES + kaddr[s]);
-        } else if (have2) {
-            load_q(nxt);
         }
         // ---- epilogue: O = acc / lr (BF16), LSE = ln2 * (m + log2 l).  A lane holds one query's values
         // in pieces of 8 bytes; they go through the same LDS region (32 rows of 256 bytes, 16-byte units
