@@ -782,8 +782,19 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
             qk_only(sa, stage_off(0));
             qk_only(sb, stage_off(1));
             TRACE_MARK(2);
-            // P(0): through the masked path, which also handles an empty first block and sets the reference
-            softmax_masked(sa, 0);
+            // P(0).  A first block without masked keys (every one but a causal item's diagonal start or a
+            // short tail) takes its maximum as the reference and has nothing to rescale yet; the masked
+            // path also handles an empty first block.
+            if (n_unm > 0) {
+                float mx = max3(sa[0][0], sa[0][1], sa[0][2]);
+#pragma unroll
+                for (int i = 3; i < 31; i += 2) mx = max3(mx, sa[i >> 4][i & 15], sa[(i + 1) >> 4][(i + 1) & 15]);
+                mx = max3(mx, sa[1][15], sa[1][15]);
+                m = lane32_max(mx) * p.c;
+                l = probabilities(sa, lr);
+            } else {
+                softmax_masked(sa, 0);
+            }
             TRACE_MARK(3);
             // K(2), V(0) landed: a warm item waited for them before the epilogue of the item before, and
             // what it still has in flight are that epilogue's stores, which nothing here depends on
