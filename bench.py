@@ -76,9 +76,11 @@ def cpu_baseline(w, q, k, v, o_gpu, lse_gpu, budget_s=12.0):
     qd, kd, vd = q.double().numpy(), k.double().numpy(), v.double().numpy()
     oracle.attn_ref_rows(qd, kd, vd, rows_all[:64], w.causal, w.scale)
     done, chunk, dt = 0, 1024, 0.0
-    o_parts, l_parts = [], []
+    o_parts, l_parts, r_parts = [], [], []
     while done < len(rows_all) and dt < budget_s:
         rows = rows_all[done:done + chunk]
+        rows = rows[np.lexsort((rows[:, 2], rows[:, 1], rows[:, 0]))]    # rows of one head side by side, as a full run has them
+        r_parts.append(rows)
         t0 = time.perf_counter()
         o_ref, lse_ref = oracle.attn_ref_rows(qd, kd, vd, rows, w.causal, w.scale)
         dt += time.perf_counter() - t0
@@ -86,7 +88,7 @@ def cpu_baseline(w, q, k, v, o_gpu, lse_gpu, budget_s=12.0):
         l_parts.append(lse_ref)
         done += len(rows)
         chunk *= 2
-    rows = rows_all[:done]
+    rows = np.concatenate(r_parts)
     o_ref, lse_ref = np.concatenate(o_parts), np.concatenate(l_parts)
     i = rows[:, 2].astype(np.int64)
     nvalid = np.minimum(w.Skv, i + 1 + w.Skv - w.Sq) if w.causal else np.full_like(i, w.Skv)
