@@ -197,6 +197,14 @@ def test_scores_jump_mid_sequence(causal):
     U.check_full(q, k.to(torch.bfloat16), v, causal, SCALE, what="score jump")
 
 
+@pytest.mark.parametrize("causal", [False, True])
+def test_keys_equal_queries_diagonal_dominates(causal):
+    """K = Q: every query's own key scores far above the others, so under the causal mask the reference
+    has to be raised in the diagonal (masked) block of every query tile, item after item."""
+    q, _, v = U.rand_qkv(3, 4, 4, 1100, 1100, seed=34, q_mul=1.5)
+    U.check_full(q, q.clone(), v, causal, SCALE, what="K = Q")
+
+
 def test_huge_scores_overflow_exp():
     """Scores of several hundred: exp2 of the first guess overflows to inf, the exact path must take over."""
     q, k, v = U.rand_qkv(1, 2, 2, 640, 1024, seed=33, q_mul=64.0)
