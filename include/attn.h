@@ -52,7 +52,7 @@ enum {
  *   stream  a hipStream_t, or NULL for the default stream
  *
  * Size limits (ATTN_E_UNSUPPORTED beyond them): Sq + Skv below 2^31 - 1024,
- * and fewer than 2^27 work items, one item being 256/p query rows of p query
+ * Hq and Hkv at most 32768, and fewer than 2^27 work items, one item being 256/p query rows of p query
  * heads that share a K/V head (p = 8, 4, 2 or 1, the largest that divides
  * Hq / Hkv).  The launch uses one workgroup per compute unit of the current
  * device (all of its LDS); the first call on a device queries the device once.

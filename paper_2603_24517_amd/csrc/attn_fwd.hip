@@ -47,6 +47,7 @@
 #include <stdint.h>
 #include <math.h>
 #include <type_traits>
+#include <atomic>
 
 #include "../../include/attn.h"
 
@@ -1031,15 +1032,17 @@ int attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
     sc.ntile = (Sq + sh.tile_pos - 1) / sh.tile_pos;
     // Key/query indices and the work-item count are 32-bit in the kernel (and below 2^31 for the divisions).
     if ((int64_t)Sq + Skv + WG_ROWS + 8 * BN >= INT32_MAX) return ATTN_E_UNSUPPORTED;
+    // Byte offsets within one tile (rows x row pitch) are 32-bit in the kernel.
+    if (Hq > 32768 || Hkv > 32768) return ATTN_E_UNSUPPORTED;
     const int64_t total = (int64_t)B * Hkv * sh.chunks * sc.ntile;
     if (total + 8 >= INT32_MAX / 16) return ATTN_E_UNSUPPORTED;
     sc.total = (int)total;
 
     // Once per device: the CU count, and the opt-in that 160 KiB of dynamic LDS needs.
-    static int cus[64] = {};
+    static std::atomic<int> cus[64];          // zero-initialised; threads that race here store the same value
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return ATTN_E_LAUNCH;
-    if (!cus[dev]) {
+    if (!cus[dev].load(std::memory_order_acquire)) {
         int n = 0;
         if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0 ||
             hipFuncSetAttribute((const void *)attn_fwd_kernel<true>,
@@ -1047,10 +1050,11 @@ int attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
             hipFuncSetAttribute((const void *)attn_fwd_kernel<false>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess)
             return ATTN_E_LAUNCH;
-        cus[dev] = n;
+        cus[dev].store(n, std::memory_order_release);
     }
     // One workgroup per CU (a workgroup takes all of a CU's registers and LDS), each working through a list.
-    const int cu_slots = cus[dev] >= 8 ? cus[dev] / 8 : 1;
+    const int ncu = cus[dev].load(std::memory_order_relaxed);
+    const int cu_slots = ncu >= 8 ? ncu / 8 : 1;
     sc.per_xcd = (int)((total + 7) / 8);
     sc.split = sc.nsub = sc.sgx = sc.window = 1;
     sc.split_log2 = 0;

@@ -51,6 +51,7 @@ def _call(**kw):
     (dict(D=64), A.ATTN_E_UNSUPPORTED), (dict(D=256), A.ATTN_E_UNSUPPORTED),
     (dict(Sq=2**31 - 200, Skv=1), A.ATTN_E_UNSUPPORTED),
     (dict(B=2**20, Hq=2**10, Hkv=2**10, Sq=2**12), A.ATTN_E_UNSUPPORTED),
+    (dict(Hq=65536, Hkv=2), A.ATTN_E_UNSUPPORTED), (dict(Hq=65536, Hkv=65536), A.ATTN_E_UNSUPPORTED),
     (dict(q=4096 + 8), A.ATTN_E_ALIGN), (dict(o=16384 + 2), A.ATTN_E_ALIGN), (dict(lse=20480 + 2), A.ATTN_E_ALIGN),
     (dict(scale=float("nan")), A.ATTN_E_SCALE), (dict(scale=float("inf")), A.ATTN_E_SCALE),
     (dict(scale=-0.5), A.ATTN_E_SCALE),
