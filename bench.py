@@ -153,6 +153,10 @@ def run_workload(name, steps, warmup, with_cpu, repeats=1):
                      "kernel": "attn_fwd_kernel", "kernel_ms": kms,
                      "algorithmic_bytes": w.algorithmic_bytes},
     }
+    rc, cus, khz = A.attn_device_info()
+    out["device"] = {"name": torch.cuda.get_device_properties(0).name, "compute_units": cus if rc == 0 else None,
+                     "max_clock_mhz": khz / 1e3 if rc == 0 else None,
+                     "peak_note": "2516.6 = 256 CU x 4 SIMD x 1024 FLOP/clk x 2.4 GHz"}
     if repeats > 1:
         out["ms_std"] = float(np.std(dev_ms))
     if with_cpu:

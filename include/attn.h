@@ -82,6 +82,15 @@ int attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
 #define ATTN_MFMA_PROBE_BLOCKS 256
 int attn_mfma_probe(const void *operands, float *sink, int iters, void *stream);
 
+/*
+ * attn_device_info -- measurement aid: what the current device reports, printed by the benchmark
+ * beside the nominal peak that the metric of section 4.1 of the paper is divided by.
+ *   compute_units  out  host, number of compute units
+ *   clock_khz      out  host, peak shader clock in kHz
+ * Returns ATTN_OK, ATTN_E_NULL, or ATTN_E_LAUNCH if the device cannot be queried.
+ */
+int attn_device_info(int *compute_units, int *clock_khz);
+
 /* Static text for a return code of this library (never NULL). */
 const char *attn_strerror(int code);
 

@@ -42,6 +42,8 @@ def load():
         lib.attn_fwd.restype = ci
         lib.attn_mfma_probe.argtypes = [vp, vp, ci, vp]
         lib.attn_mfma_probe.restype = ci
+        lib.attn_device_info.argtypes = [ctypes.POINTER(ci), ctypes.POINTER(ci)]
+        lib.attn_device_info.restype = ci
         lib.attn_strerror.argtypes = [ci]
         lib.attn_strerror.restype = ctypes.c_char_p
         lib.attn_version.argtypes = []
@@ -75,6 +77,13 @@ MFMA_PROBE_BLOCKS = 256
 def attn_mfma_probe(operands, sink, iters, stream=None):
     """C-ABI call attn_mfma_probe(...): measurement aid, see include/attn.h.  Returns the status code."""
     return load().attn_mfma_probe(_ptr(operands), _ptr(sink), int(iters), stream)
+
+
+def attn_device_info():
+    """C-ABI call attn_device_info(...): (status code, compute units, peak shader clock in kHz) of the current device."""
+    cus, khz = ctypes.c_int(0), ctypes.c_int(0)
+    rc = load().attn_device_info(ctypes.byref(cus), ctypes.byref(khz))
+    return int(rc), cus.value, khz.value
 
 
 def attn_strerror(code):

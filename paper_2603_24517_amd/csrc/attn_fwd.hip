@@ -1090,6 +1090,17 @@ int attn_mfma_probe(const void *operands, float *sink, int iters, void *stream)
     return hipGetLastError() == hipSuccess ? ATTN_OK : ATTN_E_LAUNCH;
 }
 
+int attn_device_info(int *compute_units, int *clock_khz)
+{
+    if (!compute_units || !clock_khz) return ATTN_E_NULL;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(compute_units, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        hipDeviceGetAttribute(clock_khz, hipDeviceAttributeClockRate, dev) != hipSuccess)
+        return ATTN_E_LAUNCH;
+    return ATTN_OK;
+}
+
 const char *attn_strerror(int code)
 {
     switch (code) {

@@ -77,6 +77,15 @@ def test_mfma_probe_bad_arguments(args, code):
     assert A.attn_mfma_probe(*args) == code
 
 
+def test_device_info_without_a_device_reports_an_error():
+    import torch
+    rc, cus, khz = A.attn_device_info()
+    if torch.cuda.is_available():
+        assert rc == A.ATTN_OK and cus > 0 and khz > 0
+    else:
+        assert rc == A.ATTN_E_LAUNCH
+
+
 def test_row_sampler_terminates_and_is_stratified():
     from paper_2603_24517_amd import workloads as W
     small = W.WORKLOADS[W.SMALL]
