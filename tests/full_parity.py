@@ -23,17 +23,12 @@ import oracle                                           # noqa: E402
 from paper_2603_24517_amd import workloads as W         # noqa: E402
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--workload", required=True)
-    ap.add_argument("--part", default="0/1", help="k/n: the k-th of n contiguous slices of the (b, h, i) rows")
-    ap.add_argument("--chunk", type=int, default=8192)
-    ap.add_argument("--out", default=None)
-    a = ap.parse_args()
-    w = {**W.WORKLOADS, **W.PAPER_GRID}[a.workload]
-    part, nparts = (int(x) for x in a.part.split("/"))
-    assert 0 <= part < nparts
+def check_every_row(name, part=0, nparts=1, chunk=8192, log=print):
+    """Run workload `name` on the GPU and compare rows [part/nparts slice] of O and LSE with the oracle.
 
+    Returns the error figures and `pass`; raises only on NaN or a differing -inf pattern."""
+    w = {**W.WORKLOADS, **W.PAPER_GRID}[name]
+    assert 0 <= part < nparts
     t0 = time.monotonic()
     q, k, v = W.make_qkv(w)
     o_gpu, lse_gpu = U.run_gpu(q, k, v, w.causal, w.scale)
@@ -41,13 +36,13 @@ def main():
     del q, k, v
     total = w.B * w.Hq * w.Sq
     lo, hi = total * part // nparts, total * (part + 1) // nparts
-    print(f"{w.name}: rows {lo}..{hi} of {total}, oracle threads {oracle.threads()}, "
-          f"set-up {time.monotonic() - t0:.1f} s", flush=True)
+    log(f"{w.name}: rows {lo}..{hi} of {total}, oracle threads {oracle.threads()}, "
+        f"set-up {time.monotonic() - t0:.1f} s")
 
     max_abs, sum_abs, n_el, lse_max, lse_ratio, n_inf = 0.0, 0.0, 0, 0.0, 0.0, 0
     t1 = time.monotonic()
-    for c0 in range(lo, hi, a.chunk):
-        idx = np.arange(c0, min(c0 + a.chunk, hi), dtype=np.int64)
+    for c0 in range(lo, hi, chunk):
+        idx = np.arange(c0, min(c0 + chunk, hi), dtype=np.int64)
         b, rem = np.divmod(idx, w.Hq * w.Sq)
         h, i = np.divmod(rem, w.Sq)
         rows = np.stack([b, h, i], axis=1).astype(np.int32)
@@ -66,14 +61,26 @@ def main():
             lse_max = max(lse_max, float(dl.max()))
             lse_ratio = max(lse_ratio, float((dl / (U.LSE_REL * np.maximum(1.0, np.abs(lse_ref[fin])))).max()))
         done = idx[-1] + 1 - lo
-        print(f"  {done}/{hi - lo} rows, {time.monotonic() - t1:.0f} s, max_abs {max_abs:.3e}, "
-              f"mean_abs {sum_abs / n_el:.3e}, lse {lse_max:.3e}", flush=True)
+        log(f"  {done}/{hi - lo} rows, {time.monotonic() - t1:.0f} s, max_abs {max_abs:.3e}, "
+            f"mean_abs {sum_abs / n_el:.3e}, lse {lse_max:.3e}")
 
-    res = dict(workload=w.name, part=a.part, rows=hi - lo, rows_total=total, max_abs=max_abs,
+    res = dict(workload=w.name, part=f"{part}/{nparts}", rows=hi - lo, rows_total=total, max_abs=max_abs,
                mean_abs=sum_abs / max(n_el, 1), lse_max_abs=lse_max, lse_worst_ratio=lse_ratio,
                rows_without_keys=n_inf, oracle_seconds=round(time.monotonic() - t1, 1),
                bars=dict(max_abs=U.O_MAX_ABS, mean_abs=U.O_MEAN_ABS, lse_rel=U.LSE_REL))
     res["pass"] = bool(max_abs <= U.O_MAX_ABS and res["mean_abs"] <= U.O_MEAN_ABS and lse_ratio <= 1.0)
+    return res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--workload", required=True)
+    ap.add_argument("--part", default="0/1", help="k/n: the k-th of n contiguous slices of the (b, h, i) rows")
+    ap.add_argument("--chunk", type=int, default=8192)
+    ap.add_argument("--out", default=None)
+    a = ap.parse_args()
+    part, nparts = (int(x) for x in a.part.split("/"))
+    res = check_every_row(a.workload, part, nparts, a.chunk, log=lambda m: print(m, flush=True))
     line = json.dumps(res)
     print(line, flush=True)
     if a.out:

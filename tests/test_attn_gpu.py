@@ -157,6 +157,16 @@ def test_configs_sampled_rows(name):
     print(name, r, flush=True)
 
 
+@pytest.mark.parametrize("name", ["cfg2_mha_nc_b8_h16_s4096", "cfg3a_mha_c_b8_s4096_q4", "cfg3b_mha_c_b4_s8192_q4"])
+def test_configs_every_row(name):
+    """The headline workload and the two shorter causal ones: EVERY row of O and LSE against the oracle
+    (about a minute of oracle time in all; the longer workloads are checked this way by tests/full_parity.py)."""
+    from full_parity import check_every_row
+    r = check_every_row(name, chunk=65536, log=lambda m: print(m, flush=True))
+    print(r, flush=True)
+    assert r["pass"], r
+
+
 def test_mfma_probe_runs_gpu():
     ops = torch.randn(12, 64, 8).to(torch.bfloat16).cuda()
     sink = torch.zeros(1, dtype=torch.float32, device="cuda")
