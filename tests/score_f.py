@@ -75,6 +75,22 @@ def geomean(xs):
     return 0.0 if any(x <= 0 for x in xs) else math.exp(sum(math.log(x) for x in xs) / len(xs))
 
 
+def record_in_lineage(path, rec):
+    """Append rec to the lineage file and decide, as section 3.2 has it, whether it is committed: only if
+    every configuration is correct and its geometric mean is at least the best committed one on the
+    same grid.  Returns (committed, best so far)."""
+    best = 0.0
+    if os.path.exists(path):
+        for line in open(path):
+            prev = json.loads(line)
+            if prev.get("committed") and prev.get("grid") == rec["grid"]:
+                best = max(best, prev["geomean"])
+    rec["committed"] = bool(rec["all_correct"] and rec["geomean"] >= best)
+    with open(path, "a") as f:
+        f.write(json.dumps(rec) + "\n")
+    return rec["committed"], best
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--grid", default="baseline", choices=["baseline", "paper", "tiny"])
@@ -104,16 +120,8 @@ def main():
            "all_correct": all(r["correct"] for r in res), "scores": res}
     verdict = "n/a (no lineage file)"
     if args.lineage:
-        best = 0.0
-        if os.path.exists(args.lineage):
-            for line in open(args.lineage):
-                prev = json.loads(line)
-                if prev.get("committed") and prev.get("grid") == args.grid:
-                    best = max(best, prev["geomean"])
-        rec["committed"] = bool(rec["all_correct"] and g >= best)
-        verdict = f"{'COMMIT' if rec['committed'] else 'REJECT'} (best so far {best:.1f})"
-        with open(args.lineage, "a") as f:
-            f.write(json.dumps(rec) + "\n")
+        committed, best = record_in_lineage(args.lineage, rec)
+        verdict = f"{'COMMIT' if committed else 'REJECT'} (best so far {best:.1f})"
     print(f"geomean f = {g:.1f} TFLOPS over {len(res)} configurations; all correct: {rec['all_correct']}; {verdict}")
     print(json.dumps({"geomean": g, "all_correct": rec["all_correct"], "n": len(res)}))
 
