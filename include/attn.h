@@ -55,7 +55,10 @@ enum {
  * Hq and Hkv at most 32768, and fewer than 2^27 work items, one item being 256/p query rows of p query
  * heads that share a K/V head (p = 8, 4, 2 or 1, the largest that divides
  * Hq / Hkv).  The launch uses one workgroup per compute unit of the current
- * device (all of its LDS); the first call on a device queries the device once.
+ * device (all of its LDS); the first call on a device queries the device once
+ * and sets a function attribute, so make one ordinary call on a device before
+ * recording attn_fwd into a HIP graph (later calls are one kernel launch and
+ * nothing else, and replay correctly).
  *
  * Inputs and outputs must not overlap and must stay alive until the stream
  * reaches the end of the kernel.  The call only enqueues work.  Every

@@ -128,6 +128,35 @@ def test_deterministic_and_stream_gpu():
     assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
 
 
+def test_launch_recorded_in_a_hip_graph_replays_identically():
+    """attn_fwd only enqueues one kernel, so (after one ordinary call on the device) it can be recorded
+    into a HIP graph; every replay, with other work and synchronisations in between, must reproduce the
+    directly launched result bit for bit."""
+    B, Hq, Hkv, Sq, Skv = 2, 8, 2, 700, 900
+    q, k, v = U.rand_qkv(B, Hq, Hkv, Sq, Skv, seed=28)
+    o_ref, lse_ref = U.run_gpu(q, k, v, True, SCALE)            # also the first call on the device
+    dev = torch.device("cuda:0")
+    qd, kd, vd = q.to(dev), k.to(dev), v.to(dev)
+    o = torch.zeros_like(qd)
+    lse = torch.zeros((B, Hq, Sq), dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        rc = A.attn_fwd(qd, kd, vd, o, lse, B, Hq, Hkv, Sq, Skv, 128, True, SCALE,
+                        torch.cuda.current_stream().cuda_stream)
+    assert rc == 0, A.attn_strerror(rc)
+    for rep in range(4):
+        o.fill_(float("nan"))
+        lse.fill_(float("nan"))
+        other = (qd.float() * 2).sum()                          # unrelated eager work between the replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(o.cpu().double().numpy(), o_ref), f"replay {rep}: O differs"
+        assert np.array_equal(lse.cpu().double().numpy(), lse_ref), f"replay {rep}: LSE differs"
+        assert torch.isfinite(other)
+
+
 def test_attention_wrapper_gpu():
     q, k, v = U.rand_qkv(1, 2, 2, 64, 64, seed=27)
     o, lse = A.attention(q.cuda(), k.cuda(), v.cuda(), causal=True)
