@@ -196,6 +196,26 @@ def test_configs_every_row(name):
     assert r["pass"], r
 
 
+# Shapes at the far ends of each axis (B, Hq, Hkv, Sq, Skv, causal, q_mul): one head with 1024 key blocks, a
+# group of 128 query heads on one K/V head, many tiny batch entries, a very long Q against a short K/V and the
+# reverse.  Sampled rows (stratified), every valid key of each.
+EXTREMES = [
+    (1, 1, 1, 65536, 65536, False, 1.0), (1, 1, 1, 65536, 65536, True, 1.0), (1, 128, 1, 1024, 1024, True, 1.0),
+    (300, 2, 2, 256, 256, True, 4.0), (1, 2, 2, 100000, 333, False, 1.0), (1, 2, 2, 333, 100000, True, 1.0),
+]
+
+
+@pytest.mark.parametrize("case", EXTREMES, ids=lambda c: "x".join(map(str, c[:5])) + ("-causal" if c[5] else "-full"))
+def test_extreme_shapes_sampled_rows(case):
+    B, Hq, Hkv, Sq, Skv, causal, q_mul = case
+    w = W.custom("extreme", B, Hq, Hkv, Sq, Skv, causal=causal, seed=700 + EXTREMES.index(case), q_mul=q_mul)
+    q, k, v = W.make_qkv(w)
+    rows = W.sample_rows(w, 2500)
+    print(f"case {case}: {len(rows)} rows", flush=True)
+    r = U.check_rows(q, k, v, rows, causal, SCALE, what=str(case))
+    print(r, flush=True)
+
+
 def test_mfma_probe_runs_gpu():
     ops = torch.randn(12, 64, 8).to(torch.bfloat16).cuda()
     sink = torch.zeros(1, dtype=torch.float32, device="cuda")
