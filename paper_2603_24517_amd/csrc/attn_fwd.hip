@@ -943,11 +943,25 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
             const size_t o_row_bytes = (size_t)Hq * HD * 2;
             unsigned char *og = (unsigned char *)(cold().o + ((size_t)((size_t)b * Sq + q0) * Hq + head) * HD);
             const int rows = Sq - q0;               // rows of this wavefront that exist
+            // (the row pitch is below 2^23 bytes, so the lane's first offset fits 32 bits; the rest are additions)
+            unsigned char *gp = og + ((uint32_t)orow * (uint32_t)o_row_bytes + 16u * (uint32_t)ounit);
+            const size_t gstep = 4 * o_row_bytes;
+            if (rows >= 32) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int row = 4 * i + orow;
-                const u32x4 val = *(const LDS_AS u32x4 *)(lds + ob + row * ROW_BYTES + ((ounit ^ (row & 15)) << 4));
-                if (row < rows) *(u32x4 *)(og + row * o_row_bytes + 16 * ounit) = val;
+                for (int i = 0; i < 8; ++i) {
+                    const int row = 4 * i + orow;
+                    const u32x4 val = *(const LDS_AS u32x4 *)(lds + ob + row * ROW_BYTES + ((ounit ^ (row & 15)) << 4));
+                    *(u32x4 *)gp = val;
+                    gp += gstep;
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const int row = 4 * i + orow;
+                    const u32x4 val = *(const LDS_AS u32x4 *)(lds + ob + row * ROW_BYTES + ((ounit ^ (row & 15)) << 4));
+                    if (row < rows) *(u32x4 *)gp = val;
+                    gp += gstep;
+                }
             }
             if (l32 < rows && hh == 0) {
                 const float lse = lt > 0.0f ? (m + __builtin_amdgcn_logf(lt)) * 0.6931471805599453f : -INFINITY;
