@@ -29,39 +29,83 @@ METRIC = "attention fwd TFLOPS (BF16, D=128) and % of MI355X dense BF16 MFMA pea
 
 
 def mfma_probe():
-    """What a bare MFMA loop sustains on this board for all-zero and for N(0,1) BF16 operands (context for `frac`)."""
+    """What the matrix pipe sustains on this board, and at which shader clock (context for `frac`).
+
+    A bare loop of v_mfma_f32_32x32x16_bf16 on register operands at 1, 2 and 4 wavefronts per SIMD, for
+    all-zero and for N(0,1) BF16 operands; then, at the attention kernel's 2 wavefronts per SIMD and with
+    N(0,1) operands, the same loop with the work that accompanies every MFMA in the attention kernel added
+    step by step: the softmax's vector instructions, the LDS read of one operand, the tile requests.  The
+    last of these is the ceiling of THIS instruction mix with a matrix pipe that never waits."""
+    from paper_2603_24517_amd import probe as P
     dev = torch.device("cuda:0")
     stream = torch.cuda.current_stream()
     sink = torch.zeros(1, dtype=torch.float32, device=dev)
+    clocks = torch.zeros(4, dtype=torch.int64, device=dev)
     g = torch.Generator().manual_seed(7)
-    out = {}
-    iters = 2000
-    flops = A.MFMA_PROBE_BLOCKS * 4 * iters * 32 * 32768.0
-    for name, ops in (("zeros", torch.zeros(12, 64, 8)), ("normal", torch.randn(12, 64, 8, generator=g))):
-        ops = ops.to(torch.bfloat16).to(dev)
+    tiles = torch.randn(1 << 24, generator=g).to(torch.bfloat16).to(dev)         # 32 MiB of N(0,1) BF16
+    data = {"zeros": torch.zeros(12, 64, 8), "normal_0_1": torch.randn(12, 64, 8, generator=g)}
+
+    def run(ops, mode, waves):
+        iters = 4000 // waves
         for _ in range(2):
-            rc = A.attn_mfma_probe(ops, sink, iters, stream.cuda_stream)
+            rc = P.attn_probe_mfma(ops, tiles, tiles.numel() * 2, sink, clocks, mode, waves, iters, stream.cuda_stream)
             if rc != 0:
-                raise A.AttnError(rc)
+                raise RuntimeError(f"attn_probe_mfma failed ({rc})")
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record(stream)
         for _ in range(5):
-            A.attn_mfma_probe(ops, sink, iters, stream.cuda_stream)
+            P.attn_probe_mfma(ops, tiles, tiles.numel() * 2, sink, clocks, mode, waves, iters, stream.cuda_stream)
         e1.record(stream)
         torch.cuda.synchronize()
-        out[name] = flops * 5 / (e0.elapsed_time(e1) * 1e-3) * 1e-12
-    return {"unit": "TFLOP/s", "what": "bare v_mfma_f32_32x32x16_bf16 loop, register operands, 4 waves/CU",
-            "zeros": out["zeros"], "normal_0_1": out["normal"]}
+        c = clocks.cpu().numpy()
+        cycles, ticks = int(c[1] - c[0]), int(c[3] - c[2])
+        return {"tflops": P.probe_flops(waves, iters) * 5 / (e0.elapsed_time(e1) * 1e-3) * 1e-12,
+                "clock_ghz": 0.1 * cycles / ticks, "cycles_per_mfma_per_simd": cycles / (32.0 * iters * waves)}
+
+    out = {"unit": "TFLOP/s", "what": "v_mfma_f32_32x32x16_bf16 loop, register operands, 256 workgroups; "
+                                      "wN = N wavefronts per SIMD; clock = shader cycle counter / 100 MHz counter in the launch"}
+    for name, ops in data.items():
+        ops = ops.to(torch.bfloat16).to(dev)
+        out[name] = {f"w{w}": run(ops, 0, w) for w in (1, 2, 4)}
+        if name == "normal_0_1":
+            out[name]["w2_valu"] = run(ops, P.PROBE_VALU, 2)
+            out[name]["w2_valu_lds"] = run(ops, P.PROBE_VALU | P.PROBE_LDS, 2)
+            out[name]["w2_valu_lds_dma"] = run(ops, P.PROBE_VALU | P.PROBE_LDS | P.PROBE_DMA, 2)
+    out["ceiling"] = dict(out["normal_0_1"]["w2_valu_lds_dma"],
+                          what="N(0,1) operands, 2 wavefronts per SIMD, every MFMA accompanied by the attention kernel's "
+                               "vector instructions per score, LDS operand read and share of the tile requests; "
+                               "matrix pipe never idle")
+    return out
+
+
+def kernel_clock(w, qd, kd, vd, o, lse, launches=10):
+    """Shader clock and cycle count of the attention kernel on this workload: the build of the shipped kernel
+    with clock stamps (variants/libattn_clocks.so), launched back to back like the timed run."""
+    from paper_2603_24517_amd import probe as P
+    stream = torch.cuda.current_stream()
+    for _ in range(launches):
+        rc = P.variant_attn_fwd("clocks", qd, kd, vd, o, lse, w.B, w.Hq, w.Hkv, w.Sq, w.Skv, w.D, w.causal, w.scale,
+                                stream.cuda_stream)
+        if rc != 0:
+            raise A.AttnError(rc)
+    cycles, ghz = P.clocks_read()
+    return {"cycles_first_workgroup": int(cycles), "clock_ghz": ghz}
+
+
+TRAFFIC_FILE = "profiles/attn_fwd_kernel_hbm_traffic.md"
 
 
 def traffic_from_profiles(name):
-    """HBM bytes per launch from the committed counter summary (profiles/attn_fwd_kernel_hbm_traffic.md), or None."""
+    """(HBM bytes per launch, where the figure comes from) out of the committed counter summary: it is a
+    rocprofv3 --pmc measurement made beforehand, not a measurement of this run.  (None, None) if absent."""
     import re
-    path = os.path.join(ROOT, "profiles", "attn_fwd_kernel_hbm_traffic.md")
+    path = os.path.join(ROOT, TRAFFIC_FILE)
     if not os.path.exists(path):
-        return None
-    m = re.search(r"traffic_bytes_per_launch\[%s\]\s*=\s*(\d+)" % re.escape(name), open(path).read())
-    return int(m.group(1)) if m else None
+        return None, None
+    text = open(path).read()
+    m = re.search(r"traffic_bytes_per_launch\[%s\]\s*=\s*(\d+)" % re.escape(name), text)
+    c = re.search(r"kernel source at commit\s+`?([0-9a-f]{7,40})", text)
+    return (int(m.group(1)), f"{TRAFFIC_FILE}@{c.group(1) if c else 'unknown'}") if m else (None, None)
 
 
 def cpu_baseline(w, q, k, v, o_gpu, lse_gpu, budget_s=12.0):
@@ -106,7 +150,9 @@ def cpu_baseline(w, q, k, v, o_gpu, lse_gpu, budget_s=12.0):
     return base, parity
 
 
-def run_workload(name, steps, warmup, with_cpu, repeats=1):
+def run_workload(name, steps, warmup, with_cpu, repeats=1, variant=None):
+    """`variant`: time that variant build of the kernel (paper_2603_24517_amd/variants/) instead of the
+    shipped library; the line then carries "variant" and is not a benchmark result of the product."""
     w = W.WORKLOADS[name]
     dev = torch.device("cuda:0")
     q, k, v = W.make_qkv(w)
@@ -115,9 +161,14 @@ def run_workload(name, steps, warmup, with_cpu, repeats=1):
     lse = torch.empty((w.B, w.Hq, w.Sq), dtype=torch.float32, device=dev)
     stream = torch.cuda.current_stream()
 
+    entry = A.attn_fwd
+    if variant is not None:
+        from paper_2603_24517_amd import probe as PV
+        entry = lambda *a: PV.variant_attn_fwd(variant, *a)     # noqa: E731
+
     def step():
-        rc = A.attn_fwd(qd, kd, vd, o, lse, w.B, w.Hq, w.Hkv, w.Sq, w.Skv, w.D, w.causal, w.scale,
-                        stream.cuda_stream)
+        rc = entry(qd, kd, vd, o, lse, w.B, w.Hq, w.Hkv, w.Sq, w.Skv, w.D, w.causal, w.scale,
+                   stream.cuda_stream)
         if rc != 0:
             raise A.AttnError(rc)
 
@@ -140,6 +191,7 @@ def run_workload(name, steps, warmup, with_cpu, repeats=1):
     kms = float(np.mean(dev_ms))
     tflops = w.flops / (ms * 1e-3) * 1e-12
     ktflops = w.flops / (kms * 1e-3) * 1e-12
+    traffic, traffic_source = traffic_from_profiles(w.name)
     out = {
         "metric": METRIC, "value": tflops, "unit": "TFLOPS", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -149,19 +201,25 @@ def run_workload(name, steps, warmup, with_cpu, repeats=1):
                    "causal": w.causal, "q_mul": w.q_mul, "v_dist": w.v_dist, "seed": w.seed,
                    "flops_per_step": w.flops},
         "roofline": {"bound": "mfma", "achieved": ktflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": ktflops / PEAK_BF16_TFLOPS, "traffic": traffic_from_profiles(w.name),
+                     "frac": ktflops / PEAK_BF16_TFLOPS, "traffic": traffic, "traffic_source": traffic_source,
                      "kernel": "attn_fwd_kernel", "kernel_ms": kms,
                      "algorithmic_bytes": w.algorithmic_bytes},
     }
-    rc, cus, khz = A.attn_device_info()
+    from paper_2603_24517_amd import probe as P
+    rc, cus, khz = P.attn_probe_device_info()
     out["device"] = {"name": torch.cuda.get_device_properties(0).name, "compute_units": cus if rc == 0 else None,
                      "max_clock_mhz": khz / 1e3 if rc == 0 else None,
                      "peak_note": "2516.6 = 256 CU x 4 SIMD x 1024 FLOP/clk x 2.4 GHz"}
+    if variant is not None:
+        out["variant"] = variant
     if repeats > 1:
         out["ms_std"] = float(np.std(dev_ms))
     if with_cpu:
         out["cpu_baseline"], out["parity"] = cpu_baseline(w, q, k, v, o, lse)
+        out["roofline"].update(kernel_clock(w, qd, kd, vd, o, lse))
         out["mfma_probe"] = mfma_probe()
+        ceiling = out["mfma_probe"]["ceiling"]["tflops"]
+        out["roofline"]["frac_of_probe_ceiling"] = ktflops / ceiling
     return out
 
 
@@ -173,6 +231,8 @@ def main():
     ap.add_argument("--workload", default=W.HEADLINE, choices=sorted(W.WORKLOADS))
     ap.add_argument("--all", action="store_true", help="every workload, 10 repeats of --steps each")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing leg")
+    ap.add_argument("--variant", default=None,
+                    help="time a variant build of the kernel instead of the shipped one (implies --no-cpu)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain 1 GiB device copy instead (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -196,7 +256,8 @@ def main():
             steps = max(3, min(args.steps, 30))
             print(json.dumps(run_workload(n, steps, min(args.warmup, 10), not args.no_cpu, repeats=10)), flush=True)
     else:
-        print(json.dumps(run_workload(args.workload, args.steps, args.warmup, not args.no_cpu)), flush=True)
+        print(json.dumps(run_workload(args.workload, args.steps, args.warmup, not args.no_cpu and args.variant is None,
+                                      variant=args.variant)), flush=True)
 
 
 if __name__ == "__main__":

@@ -23,7 +23,7 @@ enum {
     ATTN_E_SHAPE       = -2,  /* a dimension is <= 0, or Hq is not a multiple of Hkv           */
     ATTN_E_UNSUPPORTED = -3,  /* D != 128, or a tensor too large for the kernel's index math   */
     ATTN_E_ALIGN       = -4,  /* q, k, v or o not 16-byte aligned, or lse not 4-byte aligned   */
-    ATTN_E_SCALE       = -5,  /* scale is NaN, infinite or negative                            */
+    ATTN_E_SCALE       = -5,  /* scale is NaN or infinite                                      */
     ATTN_E_LAUNCH      = -6   /* the HIP runtime refused the launch                            */
 };
 
@@ -48,7 +48,7 @@ enum {
  *   lse  out  FP32 [B, Hq, Sq]      contiguous, fully overwritten
  *   B, Hq, Hkv, Sq, Skv  > 0, Hq % Hkv == 0;  D must be 128
  *   causal  0 = no mask, otherwise lower-triangular mask as above
- *   scale   finite and >= 0 (the caller passes 1/sqrt(D))
+ *   scale   any finite value (the caller passes 1/sqrt(D))
  *   stream  a hipStream_t, or NULL for the default stream
  *
  * Size limits (ATTN_E_UNSUPPORTED beyond them): Sq + Skv below 2^31 - 1024,
@@ -68,31 +68,6 @@ enum {
 int attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
              int B, int Hq, int Hkv, int Sq, int Skv, int D,
              int causal, float scale, void *stream);
-
-/*
- * attn_mfma_probe -- measurement aid, not part of the attention path: what the matrix pipe sustains
- * on this board for given operand data, as context for the TFLOPS figure that section 4.1 of the
- * paper uses as its metric.  Launches ATTN_MFMA_PROBE_BLOCKS workgroups of 4 wavefronts; every
- * wavefront issues iters * 32 independent v_mfma_f32_32x32x16_bf16 (32768 FLOP each) on register
- * operands read once from `operands`, so one launch performs
- *     ATTN_MFMA_PROBE_BLOCKS * 4 * iters * 32 * 32768 FLOP.
- *   operands  in   device, BF16 [12, 64, 8], 16-byte aligned (8 A and 4 B operand sets per lane)
- *   sink      out  device, 1 float (written only in a case that does not occur in practice)
- *   iters     1 .. 2^20
- *   stream    a hipStream_t, or NULL
- * Enqueues only; returns ATTN_OK or a negative code after host-side checks.
- */
-#define ATTN_MFMA_PROBE_BLOCKS 256
-int attn_mfma_probe(const void *operands, float *sink, int iters, void *stream);
-
-/*
- * attn_device_info -- measurement aid: what the current device reports, printed by the benchmark
- * beside the nominal peak that the metric of section 4.1 of the paper is divided by.
- *   compute_units  out  host, number of compute units
- *   clock_khz      out  host, peak shader clock in kHz
- * Returns ATTN_OK, ATTN_E_NULL, or ATTN_E_LAUNCH if the device cannot be queried.
- */
-int attn_device_info(int *compute_units, int *clock_khz);
 
 /* Static text for a return code of this library (never NULL). */
 const char *attn_strerror(int code);

@@ -8,8 +8,7 @@ import ctypes
 import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-# ATTN_MI355X_LIB points at another build of the same library (kernel experiments); default: in-tree build
-LIB_PATH = os.environ.get("ATTN_MI355X_LIB") or os.path.join(_HERE, "libattn_mi355x.so")
+LIB_PATH = os.path.join(_HERE, "libattn_mi355x.so")
 
 ATTN_OK = 0
 ATTN_E_NULL = -1
@@ -28,27 +27,28 @@ class AttnError(RuntimeError):
         super().__init__(f"attn_fwd failed ({code}): {attn_strerror(code)}")
 
 
+def open_library(path):
+    """ctypes handle of a build of the attention library, with the argument types of include/attn.h set."""
+    if not os.path.exists(path):
+        raise ImportError(
+            f"{path} is missing: build it with `python -m paper_2603_24517_amd.build [--all]` "
+            "(there is no fallback path)")
+    lib = ctypes.CDLL(path)
+    vp, ci = ctypes.c_void_p, ctypes.c_int
+    lib.attn_fwd.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ctypes.c_float, vp]
+    lib.attn_fwd.restype = ci
+    lib.attn_strerror.argtypes = [ci]
+    lib.attn_strerror.restype = ctypes.c_char_p
+    lib.attn_version.argtypes = []
+    lib.attn_version.restype = ci
+    return lib
+
+
 def load():
     """Load the built library (never builds, never falls back)."""
     global _lib
     if _lib is None:
-        if not os.path.exists(LIB_PATH):
-            raise ImportError(
-                f"{LIB_PATH} is missing: build it with `python -m paper_2603_24517_amd.build` "
-                "(there is no fallback path)")
-        lib = ctypes.CDLL(LIB_PATH)
-        vp, ci = ctypes.c_void_p, ctypes.c_int
-        lib.attn_fwd.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ctypes.c_float, vp]
-        lib.attn_fwd.restype = ci
-        lib.attn_mfma_probe.argtypes = [vp, vp, ci, vp]
-        lib.attn_mfma_probe.restype = ci
-        lib.attn_device_info.argtypes = [ctypes.POINTER(ci), ctypes.POINTER(ci)]
-        lib.attn_device_info.restype = ci
-        lib.attn_strerror.argtypes = [ci]
-        lib.attn_strerror.restype = ctypes.c_char_p
-        lib.attn_version.argtypes = []
-        lib.attn_version.restype = ci
-        _lib = lib
+        _lib = open_library(LIB_PATH)
     return _lib
 
 
@@ -69,21 +69,6 @@ def attn_fwd(q, k, v, o, lse, B, Hq, Hkv, Sq, Skv, D, causal, scale, stream=None
     return load().attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse),
                            int(B), int(Hq), int(Hkv), int(Sq), int(Skv), int(D),
                            int(bool(causal)), float(scale), stream)
-
-
-MFMA_PROBE_BLOCKS = 256
-
-
-def attn_mfma_probe(operands, sink, iters, stream=None):
-    """C-ABI call attn_mfma_probe(...): measurement aid, see include/attn.h.  Returns the status code."""
-    return load().attn_mfma_probe(_ptr(operands), _ptr(sink), int(iters), stream)
-
-
-def attn_device_info():
-    """C-ABI call attn_device_info(...): (status code, compute units, peak shader clock in kHz) of the current device."""
-    cus, khz = ctypes.c_int(0), ctypes.c_int(0)
-    rc = load().attn_device_info(ctypes.byref(cus), ctypes.byref(khz))
-    return int(rc), cus.value, khz.value
 
 
 def attn_strerror(code):

@@ -51,6 +51,37 @@
 
 #include "../../include/attn.h"
 
+// ---- Compile-time variants.  The shipped library defines none of these; each alternative is built
+// into a library of its own and goes through the same parity tests, so that the choices below can be
+// measured against what they replaced (the paper's sections 5.1 and 5.2 analyse the same two
+// decisions on its hardware).
+//
+// ATTN_SOFTMAX: how the softmax of an unmasked key block treats the running maximum.
+//   0  (shipped) probabilities against the running maximum as it stands, no search for the block's
+//      maximum; the exact path runs only if a partial row sum leaves the safe range
+//   1  block maximum every block, accumulator and row sums multiplied by alpha every block, no branch
+//   2  block maximum every block, the multiplication skipped under a wave-uniform vote when no lane's
+//      maximum rose
+//   3  block maximum every block, the reference raised (and the accumulator rescaled) only where the
+//      block maximum exceeds it by more than 8 in log2 units
+#ifndef ATTN_SOFTMAX
+#define ATTN_SOFTMAX 0
+#endif
+// ATTN_ITEM_OVERLAP: 1 (shipped) the last blocks of an item request the first tiles and the Q tile of the
+// next one; 0 every item loads its own tiles and its Q after the epilogue of the item before.
+#ifndef ATTN_ITEM_OVERLAP
+#define ATTN_ITEM_OVERLAP 1
+#endif
+// ATTN_LDS_PREFETCH: how many MFMAs ahead of its consumer an LDS operand fragment is read (shipped: 3).
+#ifndef ATTN_LDS_PREFETCH
+#define ATTN_LDS_PREFETCH 3
+#endif
+// ATTN_CLOCKS (undefined in the shipped library): the first wavefront of the first workgroup stamps the
+// shader cycle counter and the constant 100 MHz counter when it starts and when it ends, and the
+// library exports attn_clocks_read(); the benchmark derives the shader clock of a launch from them.
+static_assert(ATTN_SOFTMAX >= 0 && ATTN_SOFTMAX <= 3, "ATTN_SOFTMAX is 0, 1, 2 or 3");
+static_assert(ATTN_LDS_PREFETCH >= 1 && ATTN_LDS_PREFETCH <= 8, "ATTN_LDS_PREFETCH is 1 .. 8");
+
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -81,10 +112,16 @@ constexpr int LDS_BYTES = Q_BASE + NWAVES * Q_WAVE_BYTES;   // 160 KiB, all of a
 // Largest partial row sum (16 probabilities of one lane) the fast softmax path accepts: probabilities
 // stay below 2^14 relative to the reference maximum, far inside BF16 / FP32 range.
 constexpr float P_SUM_LIMIT = 16384.0f;
-#ifndef MAT_PREFETCH
-#define MAT_PREFETCH 3               // LDS reads run this many MFMAs ahead of their consumer
-#endif
-constexpr int wait_vmcnt(int n) { return 0x0F70 | n; }   // s_waitcnt vmcnt(n), n < 16, other counters untouched
+constexpr int MAT_PREFETCH = ATTN_LDS_PREFETCH;   // LDS reads run this many MFMAs ahead of their consumer
+// s_waitcnt vmcnt(n), n < 16, other counters untouched.  The tile requests are counted by hand: "all but
+// the newest n vector-memory operations have completed" stands for "the tiles of the iterations before
+// have landed" only while the requests are the only loads in the queue around them.  Loads complete in
+// order among themselves, but stores are not ordered with them, so a register spill (scratch stores and
+// loads of the compiler's own) between two requests would let the count fall to n while an older tile
+// load is still under way: the kernels must compile without scratch (a host-side test of the built code
+// object checks that), and the epilogue's stores are issued only after the wait that the next item's
+// first tiles need.
+constexpr int wait_vmcnt(int n) { return 0x0F70 | n; }
 constexpr int WAIT_VMCNT0 = wait_vmcnt(0);
 // end of an iteration: everything but the loads of the last REQ_AHEAD-1 iterations has landed
 constexpr int WAIT_ITER_END = wait_vmcnt((REQ_AHEAD - 1) * 2 * LPT);
@@ -144,9 +181,14 @@ struct Params {
     Sched sched;
 };
 
-__device__ __forceinline__ float lane32_max(float x) {
+// "Extreme" below is the raw score that maximises score * c: the largest one for c >= 0, the smallest
+// for c < 0 (NEG), so that the running maximum of the scaled scores is c times the extreme.
+template <bool NEG>
+__device__ __forceinline__ float ext2(float a, float b) { return NEG ? fminf(a, b) : fmaxf(a, b); }
+template <bool NEG>
+__device__ __forceinline__ float lane32_ext(float x) {
     auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    return ext2<NEG>(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 __device__ __forceinline__ float lane32_sum(float x) {
     auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
@@ -161,9 +203,11 @@ __device__ __forceinline__ float add_bf16_pair(uint32_t p, float acc) {
     const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
     return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, p), ones, acc, false);
 }
-__device__ __forceinline__ float max3(float a, float b, float c) {
+template <bool NEG>
+__device__ __forceinline__ float ext3(float a, float b, float c) {
     float r;
-    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    if (NEG) asm("v_min3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    else asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
     return r;
 }
 // 16 bytes per lane from global memory straight into LDS: lane L's data lands at lds_base + 16*L.
@@ -176,12 +220,17 @@ __device__ __forceinline__ const unsigned char *uniform_ptr(const unsigned char 
     const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
     return (const unsigned char *)(uintptr_t)(((uint64_t)hi << 32) | lo);
 }
+// Both forms write M0 and say so in their clobber lists: the compiler reserves M0 (it sets it itself
+// right before an instruction of its own that reads it) and warns that it will not preserve it across
+// the statement, which is exactly what is meant here.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void lds_dma16(const unsigned char *base, uint32_t voffset, uint32_t lds_base) {
     base = uniform_ptr(base);
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
                  : "s"(lds_base), "v"(voffset), "s"(base)
-                 : "memory");
+                 : "memory", "m0");
 }
 // The same with the LDS address given as a scalar plus a compile-time constant (one scalar instruction).
 template <int IMM>
@@ -189,8 +238,9 @@ __device__ __forceinline__ void lds_dma16_imm(const unsigned char *base, uint32_
     asm volatile("s_add_u32 m0, %0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
                  : "s"(lds_base), "v"(voffset), "s"(base), "n"(IMM)
-                 : "memory", "scc");
+                 : "memory", "scc", "m0");
 }
+#pragma clang diagnostic pop
 // Keeps the instruction that produces x at this point of the program order (no code is emitted).
 #define PIN(x) asm volatile("" : "+v"(x))
 __device__ __forceinline__ void wg_barrier() {
@@ -199,32 +249,11 @@ __device__ __forceinline__ void wg_barrier() {
     __builtin_amdgcn_sched_barrier(0);
 }
 
-#ifdef ATTN_TRACE
-// Debug build only (-DATTN_TRACE=<workgroups to record>): clock stamps of wavefront 0 of each workgroup
-// at eight points of its third item (the first two for a workgroup with fewer).
-__device__ unsigned long long g_trace[ATTN_TRACE][12];
-__device__ __forceinline__ void trace_mark(int k, int item) {
-    if (blockIdx.x < ATTN_TRACE && threadIdx.x == 0 && item <= 2)
-        g_trace[blockIdx.x][k] = __builtin_readcyclecounter();
-}
-#define TRACE_MARK(k) do { __builtin_amdgcn_sched_barrier(0); trace_mark(k, trace_item); __builtin_amdgcn_sched_barrier(0); } while (0)
-#endif
-#if defined(ATTN_TRACE) && defined(ATTN_TRACE_WAIT)
-// cycles the fast loop spends between "MFMA block done" and "barrier passed" (slot 8), in the wait alone (slot 9);
-// reading the clock three times per iteration slows the loop by about 6 %
-#define TRACE_WAIT_BEGIN() do { __builtin_amdgcn_sched_barrier(0); trace_t0 = __builtin_readcyclecounter(); __builtin_amdgcn_sched_barrier(0); } while (0)
-#define TRACE_WAIT_MID() do { __builtin_amdgcn_sched_barrier(0); trace_t1 = __builtin_readcyclecounter(); __builtin_amdgcn_sched_barrier(0); } while (0)
-#define TRACE_WAIT_END() do { __builtin_amdgcn_sched_barrier(0); { const unsigned long long t = __builtin_readcyclecounter(); trace_wait += t - trace_t0; trace_vm += trace_t1 - trace_t0; } __builtin_amdgcn_sched_barrier(0); } while (0)
-#else
-#define TRACE_WAIT_BEGIN() do { } while (0)
-#define TRACE_WAIT_MID() do { } while (0)
-#define TRACE_WAIT_END() do { } while (0)
-#endif
-#ifndef ATTN_TRACE
-#define TRACE_MARK(k) do { } while (0)
+#ifdef ATTN_CLOCKS
+__device__ unsigned long long g_clocks[4];      // cycle counter at start / end, 100 MHz counter at start / end
 #endif
 
-template <bool CAUSAL>
+template <bool CAUSAL, bool NEG>
 __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_fwd_kernel(const Params p)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
@@ -253,6 +282,9 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31;
     const int hh = lane >> 5;
+#ifdef ATTN_CLOCKS
+    if (bid == 0 && tid == 0) { g_clocks[2] = wall_clock64(); g_clocks[0] = __builtin_readcyclecounter(); }
+#endif
     const int off = p.Skv - cold().shape.Sq;                    // causal: key j valid iff j <= i + off
     const int nfull = p.Skv / BN;                               // tiles below this index are full
     const bool all_full = (p.Skv % BN) == 0;
@@ -591,12 +623,16 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
         return ls0 + ls1;
     };
     // Raise the running maximum to cover the unmasked block in s; rescale the accumulator and row sum.
-    auto raise_reference = [&](f32x16 (&s)[2]) __attribute__((always_inline)) {
-        float mx = max3(s[0][0], s[0][1], s[0][2]);
+    // Maximum of the scaled scores of an unmasked block, per query (log2 units).
+    auto block_maximum = [&](f32x16 (&s)[2]) __attribute__((always_inline)) -> float {
+        float mx = ext3<NEG>(s[0][0], s[0][1], s[0][2]);
 #pragma unroll
-        for (int i = 3; i < 31; i += 2) mx = max3(mx, s[i >> 4][i & 15], s[(i + 1) >> 4][(i + 1) & 15]);
-        mx = max3(mx, s[1][15], s[1][15]);
-        mx = lane32_max(mx) * p.c;
+        for (int i = 3; i < 31; i += 2) mx = ext3<NEG>(mx, s[i >> 4][i & 15], s[(i + 1) >> 4][(i + 1) & 15]);
+        mx = ext3<NEG>(mx, s[1][15], s[1][15]);
+        return lane32_ext<NEG>(mx) * p.c;
+    };
+    auto raise_reference = [&](f32x16 (&s)[2]) __attribute__((always_inline)) {
+        const float mx = block_maximum(s);
         const float mn = fmaxf(m, mx);
         rescale(mn, __builtin_amdgcn_exp2f(m - mn));
     };
@@ -609,16 +645,17 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
         int lim = p.Skv - 1;
         if (CAUSAL) lim = min(lim, q0 + (ln & 31) + off);
         const int kidx = blk * BN + 4 * (ln >> 5);
-        float mx = -INFINITY;
+        constexpr float NONE = NEG ? INFINITY : -INFINITY;      // extreme of no score at all
+        float mx = NONE;
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int key = kidx + 32 * t + 8 * (r >> 2) + (r & 3);
-                mx = fmaxf(mx, key <= lim ? s[t][r] : -INFINITY);
+                mx = ext2<NEG>(mx, key <= lim ? s[t][r] : NONE);
             }
-        mx = lane32_max(mx);
-        mx = (mx == -INFINITY) ? -INFINITY : mx * p.c;
+        mx = lane32_ext<NEG>(mx);
+        mx = (mx == NONE) ? -INFINITY : mx * p.c;
         if (__builtin_amdgcn_ballot_w64(mx > m) != 0) {
             const float mn = fmaxf(m, mx);
             rescale(mn, (mn == -INFINITY) ? 1.0f : __builtin_amdgcn_exp2f(m - mn));
@@ -674,9 +711,21 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
             if (CAUSAL) lim = min(lim, q0 + (ln & 31) + off);
             room = lim - blk * BN - 4 * (ln >> 5);
         }
+        // Variants 1..3 look for the block's maximum first (the classic running-maximum form); their
+        // masked blocks take the MFMA sequence and the exact masked softmax one after the other.
+        if (ATTN_SOFTMAX != 0 && MASKED) {
+            mfma_block(snxt, s0, s2, [](int) __attribute__((always_inline)) {});
+            softmax_masked(scur, blk);
+            return;
+        }
+        float mref = m;     // reference point of this block's probabilities
+        if (ATTN_SOFTMAX != 0) {
+            const float mx = block_maximum(scur);
+            mref = ATTN_SOFTMAX == 3 ? (mx > m + 8.0f ? mx : m) : fmaxf(m, mx);
+        }
         mfma_block(snxt, s0, s2, [&](int slot) __attribute__((always_inline)) {
             // element `slot` of the 32 scores of this lane: exp now, row-sum add one slot later
-            ev[slot] = __builtin_amdgcn_exp2f(__builtin_fmaf(scur[slot >> 4][slot & 15], p.c, -m));
+            ev[slot] = __builtin_amdgcn_exp2f(__builtin_fmaf(scur[slot >> 4][slot & 15], p.c, -mref));
             if (MASKED) {
                 const int r = slot & 15;
                 ev[slot] = (32 * (slot >> 4) + 8 * (r >> 2) + (r & 3) <= room) ? ev[slot] : 0.0f;
@@ -710,6 +759,19 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
 #pragma unroll
         for (int k = 0; k < 16; ++k) pb[k >> 3][k & 7] = pn[k];
         float ls = ls0 + ls1;
+        if (ATTN_SOFTMAX != 0) {
+            // the accumulator holds P(j) V(j) against the old reference: bring it to the new one
+            const float alpha = __builtin_amdgcn_exp2f(m - mref);
+            // Variant 1 multiplies every time.  Its test never fails; it stands there because with the 64
+            // multiplications in the same basic block as the MFMA sequence the register allocator spills
+            // (32 to 100 bytes per lane), and a spill inside this loop is not acceptable (see wait_vmcnt).
+            const bool raise = ATTN_SOFTMAX == 1 ? __builtin_amdgcn_ballot_w64(alpha <= 1.0f) != 0
+                                                 : __builtin_amdgcn_ballot_w64(mref > m) != 0;
+            if (raise) rescale(mref, alpha);
+            l += ls;
+            lr += lrn;
+            return;
+        }
         if (__builtin_amdgcn_ballot_w64(!(ls <= P_SUM_LIMIT)) != 0) {
             if (MASKED) {
                 softmax_masked(scur, blk);      // adds to l and lr itself
@@ -742,13 +804,8 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
         cur = geometry(grp, tile);
         load_q(cur);
     }
-#ifdef ATTN_TRACE
-    int trace_item = 0;
-    unsigned long long trace_t0 = 0, trace_t1 = 0, trace_wait = 0, trace_vm = 0;
-#endif
     bool warm = false;          // the first tiles of the item about to start were requested by the item before it
     while (have) {
-        TRACE_MARK(0);
         enter(cur);
         reset_state();
         // the item after this one
@@ -758,14 +815,13 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
         if (have2) nxt = geometry(grp, tile);
         // Its tiles K'(0..2), V'(0) ride on this item's last iterations (requests K(j+4), V(j+2) of
         // iterations j >= nblk-4), which takes four iterations to host them.
-        warm_next = have2 && nblk >= 2 + REQ_AHEAD && nxt.nblk > 0;
+        warm_next = ATTN_ITEM_OVERLAP && have2 && nblk >= 2 + REQ_AHEAD && nxt.nblk > 0;
         nx_nblk = nxt.nblk; nx_kg = nxt.kg; nx_vg = nxt.vg;
         // Its Q goes into this wavefront's LDS region now (the epilogue of the item before is done with
         // it) and into registers when this item's last block is done; being the oldest request of the
         // item, it never holds up a wait for tiles.
-        if (have2) request_q(nxt);
+        if (ATTN_ITEM_OVERLAP && have2) request_q(nxt);
 
-        TRACE_MARK(1);
         if (nblk > 0) {
             // Iteration j reads K(j+2) and V(j) and requests K(j+4) and V(j+2) into the stages of K(j+1)
             // and V(j-1), whose last readers finished before the previous barrier.  It ends by waiting until
@@ -783,28 +839,21 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
             // warm: K(0), K(1) landed before the last barrier of the item before, and Q is in registers
             qk_only(sa, stage_off(0));
             qk_only(sb, stage_off(1));
-            TRACE_MARK(2);
             // P(0).  A first block without masked keys (every one but a causal item's diagonal start or a
             // short tail) takes its maximum as the reference and has nothing to rescale yet; the masked
             // path also handles an empty first block.
             if (n_unm > 0) {
-                float mx = max3(sa[0][0], sa[0][1], sa[0][2]);
-#pragma unroll
-                for (int i = 3; i < 31; i += 2) mx = max3(mx, sa[i >> 4][i & 15], sa[(i + 1) >> 4][(i + 1) & 15]);
-                mx = max3(mx, sa[1][15], sa[1][15]);
-                m = lane32_max(mx) * p.c;
+                m = block_maximum(sa);
                 l = probabilities(sa, lr);
             } else {
                 softmax_masked(sa, 0);
             }
-            TRACE_MARK(3);
             // K(2), V(0) landed: a warm item waited for them before the epilogue of the item before, and
             // what it still has in flight are that epilogue's stores, which nothing here depends on
             if (!warm) __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
             wg_barrier();                                 // and every wavefront is done with K(0), K(1)
             issue_tile(3, false);                         // the requests of "iteration -1"
             issue_tile(1, true);
-            TRACE_MARK(4);
 
             // Blocks >= n_unm go through the masked softmax, which yields P = 0 where a key is not valid:
             // blocks masked out entirely for this wavefront, and the blocks past the end that the last
@@ -842,11 +891,8 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
             do {                                                                             \
                 fast_iteration(scur, snxt, a0, a1, a2, kp, vp);                              \
                 ATTN_ADVANCE_REQUESTS();                                                     \
-                TRACE_WAIT_BEGIN();                                                          \
                 __builtin_amdgcn_s_waitcnt(WAIT_ITER_END);                                   \
-                TRACE_WAIT_MID();                                                            \
                 wg_barrier();                                                                \
-                TRACE_WAIT_END();                                                            \
             } while (0)
             // The bulk of the fast iterations runs in a loop unrolled six times (two score buffers x three
             // stages), in which every LDS address is a register plus a constant.  That loop wants block j in
@@ -884,7 +930,6 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
             }
 #undef ATTN_FAST
 #undef ATTN_ADVANCE_REQUESTS
-            TRACE_MARK(5);
             // The last iteration of an item that warms up the next one requests nothing (K'(3) would
             // land in the stage of K'(0), which is read only after this item's last barrier).
             auto iteration_end = [&](int jj) __attribute__((always_inline)) {
@@ -912,10 +957,9 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
         // waited for here, before the epilogue's stores join the queue, so that its first barrier can
         // publish them.
         __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
-        TRACE_MARK(6);
 
         // ---- Q of the next item into registers, from this wavefront's LDS region
-        if (have2) {
+        if (ATTN_ITEM_OVERLAP && have2) {
 #pragma unroll
             for (int s = 0; s < 8; ++s)
                 qf[s] = *(const LDS_AS bf16x8 *)(lds + Q_BASE + wave * Q_WAVE_BYTES + kaddr[s]);
@@ -968,48 +1012,17 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
                 cold().lse[((size_t)b * Hq + head) * Sq + q0 + l32] = lse;
             }
         }
-        TRACE_MARK(7);
-#ifdef ATTN_TRACE
-        if (blockIdx.x < ATTN_TRACE && threadIdx.x == 0 && trace_item <= 2) { g_trace[blockIdx.x][8] = trace_wait; g_trace[blockIdx.x][9] = trace_vm; }
-        trace_wait = 0; trace_vm = 0;
-        ++trace_item;
-#endif
 
+        if (!ATTN_ITEM_OVERLAP && have2) load_q(nxt);
         ring0 = (ring0 + nblk) % NSTAGE;
         warm = warm_next;
         have = have2;
         r = r2;
         cur = nxt;
     }
-}
-
-// Measurement aid: a loop of independent 32x32x16 BF16 MFMAs on register operands read once from
-// `operands` (12 x 64 lanes x 8 BF16).  No LDS, no vector arithmetic, no memory traffic in the loop:
-// what it sustains is the matrix-pipe rate the board's power management allows for that data.
-__global__ __launch_bounds__(256) void mfma_probe_kernel(const bf16x8 *operands, float *sink, int iters)
-{
-    bf16x8 a[8], b[4];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) a[i] = operands[i * 64 + (threadIdx.x & 63)];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) b[i] = operands[(8 + i) * 64 + (threadIdx.x & 63)];
-    f32x16 c[4];
-#pragma unroll
-    for (int n = 0; n < 4; ++n)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) c[n][r] = 0.0f;
-    for (int it = 0; it < iters; ++it) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-#pragma unroll
-            for (int n = 0; n < 4; ++n) c[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[n], c[n], 0, 0, 0);
-    }
-    float s = 0.0f;
-#pragma unroll
-    for (int n = 0; n < 4; ++n)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s += c[n][r];
-    if (s == 123.456f) sink[0] = s;     // keeps the loop alive; practically never true
+#ifdef ATTN_CLOCKS
+    if (bid == 0 && tid == 0) { g_clocks[1] = __builtin_readcyclecounter(); g_clocks[3] = wall_clock64(); }
+#endif
 }
 
 }  // namespace
@@ -1024,7 +1037,7 @@ int attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
     if (B <= 0 || Hq <= 0 || Hkv <= 0 || Sq <= 0 || Skv <= 0 || D <= 0) return ATTN_E_SHAPE;
     if (Hq % Hkv != 0) return ATTN_E_SHAPE;
     if (D != HD) return ATTN_E_UNSUPPORTED;
-    if (!(scale >= 0.0f) || isinf(scale)) return ATTN_E_SCALE;
+    if (!isfinite(scale)) return ATTN_E_SCALE;
     if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o) & 15) return ATTN_E_ALIGN;
     if ((uintptr_t)lse & 3) return ATTN_E_ALIGN;
 
@@ -1059,9 +1072,13 @@ int attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
     if (!cus[dev].load(std::memory_order_acquire)) {
         int n = 0;
         if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0 ||
-            hipFuncSetAttribute((const void *)attn_fwd_kernel<true>,
+            hipFuncSetAttribute((const void *)attn_fwd_kernel<true, false>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess ||
-            hipFuncSetAttribute((const void *)attn_fwd_kernel<false>,
+            hipFuncSetAttribute((const void *)attn_fwd_kernel<false, false>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess ||
+            hipFuncSetAttribute((const void *)attn_fwd_kernel<true, true>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess ||
+            hipFuncSetAttribute((const void *)attn_fwd_kernel<false, true>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess)
             return ATTN_E_LAUNCH;
         cus[dev].store(n, std::memory_order_release);
@@ -1087,32 +1104,17 @@ int attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
     sc.slots = sc.per_xcd < cu_slots ? sc.per_xcd : cu_slots;
     const dim3 grid((unsigned)(sc.slots * 8)), block(NTHREADS);
     hipStream_t st = (hipStream_t)stream;
-    if (causal)
-        hipLaunchKernelGGL(attn_fwd_kernel<true>, grid, block, LDS_BYTES, st, p);
+    // a negative scale turns the running maximum of the scaled scores into c times the smallest raw score
+    const bool neg = scale < 0.0f;
+    if (causal && neg)
+        hipLaunchKernelGGL((attn_fwd_kernel<true, true>), grid, block, LDS_BYTES, st, p);
+    else if (causal)
+        hipLaunchKernelGGL((attn_fwd_kernel<true, false>), grid, block, LDS_BYTES, st, p);
+    else if (neg)
+        hipLaunchKernelGGL((attn_fwd_kernel<false, true>), grid, block, LDS_BYTES, st, p);
     else
-        hipLaunchKernelGGL(attn_fwd_kernel<false>, grid, block, LDS_BYTES, st, p);
+        hipLaunchKernelGGL((attn_fwd_kernel<false, false>), grid, block, LDS_BYTES, st, p);
     return hipGetLastError() == hipSuccess ? ATTN_OK : ATTN_E_LAUNCH;
-}
-
-int attn_mfma_probe(const void *operands, float *sink, int iters, void *stream)
-{
-    if (!operands || !sink) return ATTN_E_NULL;
-    if (iters <= 0 || iters > (1 << 20)) return ATTN_E_SHAPE;
-    if ((uintptr_t)operands & 15) return ATTN_E_ALIGN;
-    hipLaunchKernelGGL(mfma_probe_kernel, dim3(ATTN_MFMA_PROBE_BLOCKS), dim3(256), 0, (hipStream_t)stream,
-                       (const bf16x8 *)operands, sink, iters);
-    return hipGetLastError() == hipSuccess ? ATTN_OK : ATTN_E_LAUNCH;
-}
-
-int attn_device_info(int *compute_units, int *clock_khz)
-{
-    if (!compute_units || !clock_khz) return ATTN_E_NULL;
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(compute_units, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-        hipDeviceGetAttribute(clock_khz, hipDeviceAttributeClockRate, dev) != hipSuccess)
-        return ATTN_E_LAUNCH;
-    return ATTN_OK;
 }
 
 const char *attn_strerror(int code)
@@ -1123,12 +1125,21 @@ const char *attn_strerror(int code)
     case ATTN_E_SHAPE:       return "bad shape: every dimension must be positive and Hq a multiple of Hkv";
     case ATTN_E_UNSUPPORTED: return "unsupported: head dimension must be 128 and sizes must fit 32-bit indices";
     case ATTN_E_ALIGN:       return "misaligned pointer: q, k, v, o need 16-byte and lse 4-byte alignment";
-    case ATTN_E_SCALE:       return "scale must be finite and non-negative";
+    case ATTN_E_SCALE:       return "scale must be finite";
     case ATTN_E_LAUNCH:      return "kernel launch failed";
     default:                 return "unknown attn error code";
     }
 }
 
-int attn_version(void) { return 1000; }
+int attn_version(void) { return 1001; }
+
+#ifdef ATTN_CLOCKS
+// Waits for the device, then copies the stamps of the last launch to the host (4 x 64-bit).
+int attn_clocks_read(unsigned long long *out)
+{
+    if (!out) return ATTN_E_NULL;
+    return hipMemcpyFromSymbol(out, HIP_SYMBOL(g_clocks), sizeof(g_clocks)) == hipSuccess ? ATTN_OK : ATTN_E_LAUNCH;
+}
+#endif
 
 }  // extern "C"

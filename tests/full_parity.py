@@ -69,6 +69,10 @@ def check_every_row(name, part=0, nparts=1, chunk=8192, log=print):
                rows_without_keys=n_inf, oracle_seconds=round(time.monotonic() - t1, 1),
                bars=dict(max_abs=U.O_MAX_ABS, mean_abs=U.O_MEAN_ABS, lse_rel=U.LSE_REL))
     res["pass"] = bool(max_abs <= U.O_MAX_ABS and res["mean_abs"] <= U.O_MEAN_ABS and lse_ratio <= 1.0)
+    ceiling = U.CEILINGS.get(w.name)
+    if ceiling is not None:             # the regression ceiling of the workload, where it has one
+        res["ceiling"] = dict(max_abs=ceiling[0], mean_abs=ceiling[1])
+        res["pass"] = bool(res["pass"] and max_abs <= ceiling[0] and res["mean_abs"] <= ceiling[1])
     return res
 
 

@@ -9,10 +9,31 @@ from paper_2603_24517_amd import workloads as W
 O_MAX_ABS = 2e-2       # tolerance on BF16 O against the unrounded FP64 oracle
 O_MEAN_ABS = 2e-3
 LSE_REL = 1e-3         # |dLSE| <= LSE_REL * max(1, |LSE_ref|)
+# On top of the stated bars (which are absolute, so loose where the outputs are small):
+# the largest O error of a compared set stays below 2^-7 of the largest |O| of that set -- BF16 rounding
+# of the output alone is up to 2^-9 of it, rounding of the weights adds about as much again;
+O_REL_TO_LARGEST = 2.0 ** -7
+# and the benchmark workloads stay within twice the errors measured over EVERY row of each with the
+# kernel as first committed (max-abs, mean-abs; never above the stated bars), so that a change that
+# degrades accuracy tenfold cannot pass unnoticed where |O| is a few hundredths.
+CEILINGS = {
+    "cfg1_mha_nc_b1_h4_s512": (2.8e-3, 2.6e-4),
+    "cfg2_mha_nc_b8_h16_s4096": (1.5e-3, 1.0e-4),
+    "cfg3a_mha_c_b8_s4096_q4": (2.0e-2, 1.3e-3),
+    "cfg3b_mha_c_b4_s8192_q4": (2.0e-2, 1.2e-3),
+    "cfg3c_mha_c_b2_s16384_q4": (2.0e-2, 1.15e-3),
+    "cfg3d_mha_c_b1_s32768_q4": (2.0e-2, 1.05e-3),
+    "cfg4a_gqa4_c_b4_s8192": (1.96e-2, 1.25e-4),
+    "cfg4b_gqa4_c_b2_s16384": (1.6e-2, 9.0e-5),
+    "cfg4c_gqa4_c_b1_s32768": (1.6e-2, 6.5e-5),
+    "cfg5a_gqa8_c_b1_s32768_vu": (5.4e-3, 3.8e-5),
+    "cfg5b_gqa8_nc_b1_s32768_vu": (2.6e-4, 1.9e-5),
+}
 
 
-def run_gpu(q, k, v, causal, scale, stream=None):
-    """q, k, v: CPU BF16 tensors [B,S,H,D].  Returns (O float64 numpy, LSE float64 numpy) from the HIP path."""
+def run_gpu(q, k, v, causal, scale, stream=None, attn_fwd=None):
+    """q, k, v: CPU BF16 tensors [B,S,H,D].  Returns (O float64 numpy, LSE float64 numpy) from the HIP path
+    (`attn_fwd`: the C-ABI entry point to call; default the shipped library's)."""
     dev = torch.device("cuda:0")
     qd, kd, vd = q.to(dev), k.to(dev), v.to(dev)
     B, Sq, Hq, D = q.shape
@@ -20,14 +41,14 @@ def run_gpu(q, k, v, causal, scale, stream=None):
     o = torch.full_like(qd, float("nan"))
     lse = torch.full((B, Hq, Sq), float("nan"), dtype=torch.float32, device=dev)
     st = torch.cuda.current_stream().cuda_stream if stream is None else stream
-    rc = A.attn_fwd(qd, kd, vd, o, lse, B, Hq, Hkv, Sq, Skv, D, causal, scale, st)
+    rc = (attn_fwd or A.attn_fwd)(qd, kd, vd, o, lse, B, Hq, Hkv, Sq, Skv, D, causal, scale, st)
     assert rc == 0, A.attn_strerror(rc)
     torch.cuda.synchronize()
     return o.cpu().double().numpy(), lse.cpu().double().numpy()
 
 
-def compare(o_gpu, lse_gpu, o_ref, lse_ref, what=""):
-    """Gate O and LSE; returns the error figures."""
+def compare(o_gpu, lse_gpu, o_ref, lse_ref, what="", ceiling=None):
+    """Gate O and LSE; returns the error figures.  `ceiling`: (max-abs, mean-abs) of CEILINGS, if the set has one."""
     assert not np.isnan(o_gpu).any(), f"{what}: NaN in O"
     assert not np.isnan(lse_gpu).any(), f"{what}: NaN in LSE"
     err = np.abs(o_gpu - o_ref)
@@ -43,20 +64,27 @@ def compare(o_gpu, lse_gpu, o_ref, lse_ref, what=""):
     assert res["max_abs"] <= O_MAX_ABS, f"{what}: O max-abs {res['max_abs']:.3e}"
     assert res["mean_abs"] <= O_MEAN_ABS, f"{what}: O mean-abs {res['mean_abs']:.3e}"
     assert res["lse_worst_ratio"] <= 1.0, f"{what}: LSE error {res['lse_max']:.3e}"
+    largest = float(np.abs(o_ref).max()) if o_ref.size else 0.0
+    res["max_abs_rel_to_largest"] = res["max_abs"] / largest if largest > 0 else 0.0
+    assert res["max_abs"] <= O_REL_TO_LARGEST * largest + 1e-30, \
+        f"{what}: O max-abs {res['max_abs']:.3e} above 2^-7 of the largest |O| = {largest:.3e}"
+    if ceiling is not None:
+        assert res["max_abs"] <= ceiling[0] and res["mean_abs"] <= ceiling[1], \
+            f"{what}: O errors {res['max_abs']:.3e} / {res['mean_abs']:.3e} above the regression ceiling {ceiling}"
     return res
 
 
-def check_full(q, k, v, causal, scale, what=""):
+def check_full(q, k, v, causal, scale, what="", ceiling=None, attn_fwd=None):
     o_ref, lse_ref = oracle.attn_ref(q, k, v, causal, scale)
-    o, lse = run_gpu(q, k, v, causal, scale)
-    return compare(o, lse, o_ref, lse_ref, what)
+    o, lse = run_gpu(q, k, v, causal, scale, attn_fwd=attn_fwd)
+    return compare(o, lse, o_ref, lse_ref, what, ceiling)
 
 
-def check_rows(q, k, v, rows, causal, scale, what=""):
+def check_rows(q, k, v, rows, causal, scale, what="", ceiling=None, attn_fwd=None):
     o_ref, lse_ref = oracle.attn_ref_rows(q, k, v, rows, causal, scale)
-    o, lse = run_gpu(q, k, v, causal, scale)
+    o, lse = run_gpu(q, k, v, causal, scale, attn_fwd=attn_fwd)
     b, h, i = rows[:, 0], rows[:, 1], rows[:, 2]
-    return compare(o[b, i, h], lse[b, h, i], o_ref, lse_ref, what)
+    return compare(o[b, i, h], lse[b, h, i], o_ref, lse_ref, what, ceiling)
 
 
 def rand_qkv(B, Hq, Hkv, Sq, Skv, seed, q_mul=1.0, D=128):

@@ -294,9 +294,26 @@ def pin_batch_and_head_independence(orc):
     assert not np.allclose(o[1], o2[1])
 
 
+def pin_probs_values_against_brute_force(orc):
+    """The weights entry, for rows of several batch entries and heads: exp(scale s_j) / sum, by scalar loops."""
+    B, Hq, Hkv, Sq, Skv, D = 2, 6, 3, 5, 7, 3
+    q, k, _ = _qkv(B, Hq, Hkv, Sq, Skv, D, 330)
+    scale = 0.6
+    for causal in (False, True):
+        for (b, h, i) in [(1, 4, 2), (0, 5, 0), (1, 0, 4), (1, 3, 3)]:
+            g = h // (Hq // Hkv)
+            n = _nvalid(i, Sq, Skv, causal)
+            e = [math.exp(scale * sum(q[b, i, h, d] * k[b, j, g, d] for d in range(D))) for j in range(n)]
+            want = np.zeros(Skv)
+            want[:n] = np.array(e) / sum(e)
+            got = orc.attn_ref_probs(q, k, b, h, i, causal, scale)
+            assert np.allclose(got, want, atol=1e-14, rtol=0), (causal, b, h, i)
+
+
 ALL_PINS = [
     pin_probs_sum_to_one, pin_constant_v, pin_zero_q_gives_mean, pin_causal_row0,
     pin_brute_force_tiny, pin_library_sdpa, pin_causal_is_prefix, pin_gqa_is_repeated_mha,
     pin_key_permutation, pin_split_merge, pin_score_shift, pin_dominant_key,
     pin_golden_two_keys, pin_rows_entry_matches_full, pin_batch_and_head_independence,
+    pin_probs_values_against_brute_force,
 ]

@@ -11,18 +11,40 @@ import paper_2603_24517_amd as A
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _declared_symbols():
-    text = open(os.path.join(ROOT, "include", "attn.h")).read()
+def _declared_symbols(header):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(attn_[a-z_0-9]+)\s*\(", text)))
 
 
+def _exported_symbols(path):
+    """The attn_* functions a shared object defines (dynamic symbol table, via nm)."""
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--defined-only", path], check=True, capture_output=True, text=True).stdout
+    return sorted({ln.split()[-1] for ln in out.splitlines() if ln.split()[-1].startswith("attn_")})
+
+
 def test_header_symbols_exported():
-    syms = _declared_symbols()
-    assert {"attn_fwd", "attn_strerror", "attn_version"} <= set(syms)
+    syms = _declared_symbols("attn.h")
+    assert syms == ["attn_fwd", "attn_strerror", "attn_version"]
     lib = ctypes.CDLL(A.LIB_PATH)
     for s in syms:
         assert hasattr(lib, s), f"{s} declared in include/attn.h but not exported"
+    # and the attention library exports nothing beyond its header
+    assert _exported_symbols(A.LIB_PATH) == syms
+
+
+def test_probe_header_symbols_exported():
+    from paper_2603_24517_amd import build as B
+    syms = _declared_symbols("attn_probe.h")
+    assert syms == ["attn_clocks_read", "attn_probe_device_info", "attn_probe_mfma"]
+    assert _exported_symbols(B.PROBE_LIB) == ["attn_probe_device_info", "attn_probe_mfma"]
+    # every variant build keeps the C ABI of include/attn.h; the clocks build adds its reader
+    for name in B.VARIANTS:
+        want = ["attn_fwd", "attn_strerror", "attn_version"]
+        if name == "clocks":
+            want = ["attn_clocks_read"] + want
+        assert _exported_symbols(B.variant_path(name)) == sorted(want), name
 
 
 def test_version_and_strerror():
@@ -54,7 +76,7 @@ def _call(**kw):
     (dict(Hq=65536, Hkv=2), A.ATTN_E_UNSUPPORTED), (dict(Hq=65536, Hkv=65536), A.ATTN_E_UNSUPPORTED),
     (dict(q=4096 + 8), A.ATTN_E_ALIGN), (dict(o=16384 + 2), A.ATTN_E_ALIGN), (dict(lse=20480 + 2), A.ATTN_E_ALIGN),
     (dict(scale=float("nan")), A.ATTN_E_SCALE), (dict(scale=float("inf")), A.ATTN_E_SCALE),
-    (dict(scale=-0.5), A.ATTN_E_SCALE),
+    (dict(scale=float("-inf")), A.ATTN_E_SCALE),
 ])
 def test_bad_arguments_rejected_on_host(kw, code):
     # none of these calls may reach the device: the pointers are fake addresses
@@ -68,22 +90,29 @@ def test_no_cpu_fallback():
         A.attention(x, x, x)
 
 
-@pytest.mark.parametrize("args,code", [
-    ((None, 4096, 10), A.ATTN_E_NULL), ((4096, None, 10), A.ATTN_E_NULL),
-    ((4096, 8192, 0), A.ATTN_E_SHAPE), ((4096, 8192, 1 << 21), A.ATTN_E_SHAPE),
-    ((4096 + 4, 8192, 10), A.ATTN_E_ALIGN),
+@pytest.mark.parametrize("kw", [
+    dict(operands=None), dict(sink=None), dict(clocks=None), dict(operands=4096 + 4), dict(clocks=12288 + 4),
+    dict(iters=0), dict(iters=(1 << 20) + 1), dict(waves=3), dict(waves=0), dict(mode=8), dict(mode=-1),
+    dict(mode=4, tiles=None), dict(mode=4, tiles=1 << 20, tiles_bytes=3 << 20), dict(mode=4, tiles=1 << 20, tiles_bytes=1 << 19),
+    dict(mode=5, tiles=(1 << 20) + 8, tiles_bytes=1 << 20),
 ])
-def test_mfma_probe_bad_arguments(args, code):
-    assert A.attn_mfma_probe(*args) == code
+def test_probe_bad_arguments_rejected_on_host(kw):
+    from paper_2603_24517_amd import probe as P
+    a = dict(operands=4096, tiles=None, tiles_bytes=0, sink=8192, clocks=12288, mode=0, waves=2, iters=10)
+    a.update(kw)
+    rc = P.attn_probe_mfma(a["operands"], a["tiles"], a["tiles_bytes"], a["sink"], a["clocks"], a["mode"],
+                           a["waves"], a["iters"])
+    assert rc == -1          # ATTN_PROBE_E_ARG: no launch was attempted with these fake addresses
 
 
 def test_device_info_without_a_device_reports_an_error():
     import torch
-    rc, cus, khz = A.attn_device_info()
+    from paper_2603_24517_amd import probe as P
+    rc, cus, khz = P.attn_probe_device_info()
     if torch.cuda.is_available():
-        assert rc == A.ATTN_OK and cus > 0 and khz > 0
+        assert rc == 0 and cus > 0 and khz > 0
     else:
-        assert rc == A.ATTN_E_LAUNCH
+        assert rc == -2      # ATTN_PROBE_E_LAUNCH
 
 
 def test_row_sampler_terminates_and_is_stratified():

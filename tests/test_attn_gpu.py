@@ -168,7 +168,7 @@ def test_attention_wrapper_gpu():
 def test_cfg1_full():
     w = W.WORKLOADS[W.SMALL]
     q, k, v = W.make_qkv(w)
-    r = U.check_full(q, k, v, w.causal, w.scale, what=w.name)
+    r = U.check_full(q, k, v, w.causal, w.scale, what=w.name, ceiling=U.CEILINGS[w.name])
     print(w.name, r, flush=True)
 
 
@@ -179,6 +179,19 @@ BIG = [n for n in W.WORKLOADS if n != W.SMALL]
 def test_configs_sampled_rows(name):
     """Full-size launch (the one bench.py times); a stratified sample of rows checked one by one."""
     w = W.WORKLOADS[name]
+    print(f"case {name}", flush=True)
+    q, k, v = W.make_qkv(w)
+    rows = W.sample_rows(w, 1536)
+    r = U.check_rows(q, k, v, rows, w.causal, w.scale, what=name, ceiling=U.CEILINGS[name])
+    print(name, r, flush=True)
+
+
+@pytest.mark.parametrize("name", sorted(W.PAPER_GRID))
+def test_paper_grid_sampled_rows(name):
+    """The rest of the paper's own benchmark grid (section 4.1: 16-head MHA, causal and not, at the four
+    (batch, sequence) points; section 4.3: 32 query heads on 8 and on 4 K/V heads): the full-size launch,
+    a stratified sample of rows checked one by one against the oracle."""
+    w = W.PAPER_GRID[name]
     print(f"case {name}", flush=True)
     q, k, v = W.make_qkv(w)
     rows = W.sample_rows(w, 1536)
@@ -216,12 +229,15 @@ def test_extreme_shapes_sampled_rows(case):
     print(r, flush=True)
 
 
-def test_mfma_probe_runs_gpu():
-    ops = torch.randn(12, 64, 8).to(torch.bfloat16).cuda()
-    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
-    assert A.attn_mfma_probe(ops, sink, 10, torch.cuda.current_stream().cuda_stream) == 0
-    torch.cuda.synchronize()
-    assert float(sink.item()) == 0.0
+@pytest.mark.parametrize("scale", [-SCALE, -1.0])
+@pytest.mark.parametrize("causal", [False, True])
+def test_negative_scale(scale, causal):
+    """A negative scale turns the largest scaled score into the smallest raw one; every path that looks
+    for a maximum (first block, masked blocks, the exact path after an overflow) has to follow."""
+    q, k, v = U.rand_qkv(2, 4, 2, 700, 900, seed=41, q_mul=2.0)
+    U.check_full(q, k, v, causal, scale, what=f"scale={scale}")
+    q, k, v = U.rand_qkv(1, 2, 2, 640, 1024, seed=42, q_mul=48.0)     # overflow of the first guess
+    U.check_full(q, k, v, causal, scale, what=f"scale={scale}, huge scores")
 
 
 def test_random_shapes_gpu():

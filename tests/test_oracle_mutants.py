@@ -34,6 +34,8 @@ MUTANTS = [
     ("max_over_all_keys_not_valid", "if (s[j] > mx) mx = s[j];", "if (fabs(s[j]) > mx) mx = fabs(s[j]);"),
     ("rows_entry_swaps_b_h", "one_row(q, k, v, rows[3 * r], rows[3 * r + 1], rows[3 * r + 2],",
      "one_row(q, k, v, rows[3 * r + 1] % B, rows[3 * r] % Hq, rows[3 * r + 2],"),
+    ("probs_entry_swaps_b_h", "one_row(q, k, zeros, b, h, i,", "one_row(q, k, zeros, h % B, b % Hq, i,"),
+    ("probs_entry_ignores_batch", "one_row(q, k, zeros, b, h, i,", "one_row(q, k, zeros, 0, h, i,"),
 ]
 
 

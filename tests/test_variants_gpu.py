@@ -1,0 +1,95 @@
+"""The variant builds of the attention kernel (one compile-time switch each, see the head of
+csrc/attn_fwd.hip) and the measurement-aid library, on the GPU: every variant goes through the same
+parity checks against the FP64 oracle as the shipped kernel, so that what is measured against the
+shipped choice (the alternatives that sections 5.1 and 5.2 of the paper weigh on its hardware) is a
+correct kernel too."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2603_24517_amd import build as B
+from paper_2603_24517_amd import probe as P
+from paper_2603_24517_amd import workloads as W
+import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+SCALE = 1.0 / math.sqrt(128)
+
+# B, Hq, Hkv, Sq, Skv, q_mul: ragged tiles, head packing, several items per workgroup, moving maxima
+SHAPES = [
+    (1, 2, 2, 300, 200, 1.0), (2, 8, 2, 333, 777, 1.0), (1, 3, 1, 700, 130, 4.0), (3, 16, 16, 520, 520, 1.0),
+    (2, 64, 8, 260, 260, 1.0), (1, 4, 4, 1500, 2100, 16.0), (40, 8, 8, 256, 256, 4.0),
+]
+
+
+def _entry(name):
+    return lambda *a: P.variant_attn_fwd(name, *a)
+
+
+@pytest.mark.parametrize("causal", [False, True], ids=["full", "causal"])
+@pytest.mark.parametrize("name", sorted(B.VARIANTS))
+def test_variant_parity_small_shapes(name, causal):
+    for n, (Bn, Hq, Hkv, Sq, Skv, q_mul) in enumerate(SHAPES):
+        print(f"variant {name} causal={causal} shape={SHAPES[n]}", flush=True)
+        q, k, v = U.rand_qkv(Bn, Hq, Hkv, Sq, Skv, seed=8100 + n, q_mul=q_mul)
+        U.check_full(q, k, v, causal, SCALE, what=f"{name} {SHAPES[n]}", attn_fwd=_entry(name))
+
+
+@pytest.mark.parametrize("name", sorted(B.VARIANTS))
+def test_variant_scores_jump_and_sorted_keys(name):
+    """Maxima that keep rising: where the variants differ from each other."""
+    q, k, v = U.rand_qkv(1, 2, 2, 2048, 2048, seed=32)
+    k = k.float()
+    k[:, 1024:] *= 40.0
+    for causal in (False, True):
+        U.check_full(q, k.to(torch.bfloat16), v, causal, SCALE, what=f"{name} score jump", attn_fwd=_entry(name))
+    S = 512
+    q = (torch.ones(1, 64, 1, 128) * 0.5).to(torch.bfloat16)
+    k = (torch.linspace(-4.0, 4.0, S).view(1, S, 1, 1) * torch.ones(1, S, 1, 128)).to(torch.bfloat16)
+    v = torch.randn(1, S, 1, 128, generator=torch.Generator().manual_seed(5)).to(torch.bfloat16)
+    U.check_full(q, k, v, False, 0.5, what=f"{name} sorted keys", attn_fwd=_entry(name))
+
+
+@pytest.mark.parametrize("name", sorted(B.VARIANTS))
+def test_variant_headline_and_short_causal_sampled_rows(name):
+    for wl in ("cfg2_mha_nc_b8_h16_s4096", "cfg3a_mha_c_b8_s4096_q4"):
+        w = W.WORKLOADS[wl]
+        print(f"variant {name} workload {wl}", flush=True)
+        q, k, v = W.make_qkv(w)
+        rows = W.sample_rows(w, 768)
+        U.check_rows(q, k, v, rows, w.causal, w.scale, what=f"{name} {wl}", ceiling=U.CEILINGS[wl],
+                     attn_fwd=_entry(name))
+
+
+def test_clocks_variant_reports_a_plausible_clock():
+    w = W.WORKLOADS["cfg2_mha_nc_b8_h16_s4096"]
+    q, k, v = (x.cuda() for x in W.make_qkv(w))
+    o = torch.empty_like(q)
+    lse = torch.empty((w.B, w.Hq, w.Sq), dtype=torch.float32, device="cuda")
+    for _ in range(3):
+        assert P.variant_attn_fwd("clocks", q, k, v, o, lse, w.B, w.Hq, w.Hkv, w.Sq, w.Skv, w.D, False, w.scale,
+                                  torch.cuda.current_stream().cuda_stream) == 0
+    cycles, ghz = P.clocks_read()
+    print(f"cycles {cycles}, clock {ghz:.3f} GHz", flush=True)
+    assert 5e5 < cycles < 5e6 and 0.5 < ghz < 2.6
+
+
+@pytest.mark.parametrize("waves", [1, 2, 4])
+@pytest.mark.parametrize("mode", range(8))
+def test_probe_runs(mode, waves):
+    ops = torch.randn(12, 64, 8, generator=torch.Generator().manual_seed(7)).to(torch.bfloat16).cuda()
+    tiles = torch.randn(1 << 20, generator=torch.Generator().manual_seed(8)).to(torch.bfloat16).cuda()   # 2 MiB
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    clocks = torch.zeros(4, dtype=torch.int64, device="cuda")
+    rc = P.attn_probe_mfma(ops, tiles, tiles.numel() * 2, sink, clocks, mode, waves, 50,
+                           torch.cuda.current_stream().cuda_stream)
+    assert rc == 0
+    torch.cuda.synchronize()
+    c = clocks.cpu().numpy()
+    assert float(sink.item()) == 0.0
+    cycles, ticks = int(c[1] - c[0]), int(c[3] - c[2])
+    # 50 x 32 MFMAs of 32 matrix-pipe cycles per wavefront, `waves` wavefronts sharing a pipe
+    assert cycles >= 50 * 32 * 32 * waves * 0.9 and ticks > 0
+    assert 0.5 < 0.1 * cycles / ticks < 2.6
