@@ -31,6 +31,9 @@ VARIANTS = {
     "softmax_blockmax_vote": ["-DATTN_SOFTMAX=2"],
     "softmax_blockmax_threshold": ["-DATTN_SOFTMAX=3"],
     "no_item_overlap": ["-DATTN_ITEM_OVERLAP=0"],
+    # every launch through the 256-row kernel / every launch through the split-key kernel for small problems
+    "no_small_path": ["-DATTN_SMALL_PATH=0"],
+    "always_small_path": ["-DATTN_SMALL_PATH=2"],
     "lds_prefetch_1": ["-DATTN_LDS_PREFETCH=1"],
     "lds_prefetch_5": ["-DATTN_LDS_PREFETCH=5"],
     # the shipped kernel plus clock stamps of its first workgroup (exports attn_clocks_read as well)

@@ -72,6 +72,12 @@
 #ifndef ATTN_ITEM_OVERLAP
 #define ATTN_ITEM_OVERLAP 1
 #endif
+// ATTN_SMALL_PATH: which launches go to the split-key kernel for small problems (at the end of this
+// file): 1 (shipped) those whose 256-row work items would occupy at most a quarter of the compute
+// units; 0 none; 2 all.
+#ifndef ATTN_SMALL_PATH
+#define ATTN_SMALL_PATH 1
+#endif
 // ATTN_LDS_PREFETCH: how many MFMAs ahead of its consumer an LDS operand fragment is read (shipped: 3).
 #ifndef ATTN_LDS_PREFETCH
 #define ATTN_LDS_PREFETCH 3
@@ -1025,6 +1031,234 @@ __global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))
 #endif
 }
 
+// ---------------------------------------------------------------------------------------------------
+// The kernel for small problems.  With 256 query rows per work item a short query sequence (or few
+// heads) leaves most compute units without work, however long the key sequence is.  Here a work item
+// is 32 query rows of one query head, and the eight wavefronts of the workgroup share its KEYS instead
+// of its rows: wavefront w takes the 32-key blocks w, w + 8, ... with a running maximum and running
+// sums of its own (the same online softmax, paper section 2.2), staging its K and V blocks through a
+// private 16 KiB of LDS, and the eight partial results are merged through LDS at the end:
+//     M = max_w m_w,  f_w = 2^(m_w - M),  O = sum_w f_w acc_w / sum_w f_w lr_w,  LSE = ln2 (M + log2 sum_w f_w l_w).
+// No barrier inside the key loop, no workspace in device memory.
+struct SplitParams {
+    const __bf16 *q, *k, *v;
+    __bf16 *o;
+    float *lse;
+    int Hq, Hkv, Sq, Skv, G;
+    int ntile;      // ceil(Sq / 32)
+    float c;        // scale * log2(e)
+};
+constexpr int SPLIT_KEYS = 32;                                  // keys per block of the split kernel
+constexpr int SPLIT_TILE_BYTES = SPLIT_KEYS * ROW_BYTES;        // 8 KiB: one K or V block
+constexpr int SPLIT_WAVE_BYTES = 2 * SPLIT_TILE_BYTES;          // per wavefront: its K block, then its V block
+constexpr int SPLIT_STATE_BASE = NWAVES * SPLIT_WAVE_BYTES;     // after them: m, l, lr of every wavefront
+constexpr int SPLIT_LDS_BYTES = SPLIT_STATE_BASE + NWAVES * 3 * 32 * 4;
+static_assert(SPLIT_WAVE_BYTES == 32 * HD * 4, "a wavefront's partial accumulator takes the place of its two blocks");
+static_assert(SPLIT_LDS_BYTES <= LDS_BYTES, "the split kernel is launched with the same dynamic LDS size");
+
+template <bool CAUSAL, bool NEG>
+__global__ __launch_bounds__(NTHREADS) void attn_fwd_split_kernel(const SplitParams p)
+{
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    LDS_AS unsigned char *lds = (LDS_AS unsigned char *)smem;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, hh = lane >> 5;
+    const int item = blockIdx.x;
+    const int tile = item % p.ntile, bh = item / p.ntile;
+    const int head = bh % p.Hq, b = bh / p.Hq;
+    const int hkv = head / p.G;
+    const int q0 = tile * 32;
+    const int off = p.Skv - p.Sq;
+    // keys 0 .. klast are valid for some row of the tile
+    int klast = p.Skv - 1;
+    if (CAUSAL) klast = min(klast, min(q0 + 31, p.Sq - 1) + off);
+    const int nb = klast < 0 ? 0 : klast / SPLIT_KEYS + 1;
+    const size_t kv_row_bytes = (size_t)p.Hkv * HD * 2;
+    const unsigned char *kg = (const unsigned char *)(p.k + ((size_t)b * p.Skv * p.Hkv + hkv) * HD);
+    const unsigned char *vg = (const unsigned char *)(p.v + ((size_t)b * p.Skv * p.Hkv + hkv) * HD);
+
+    // Q^T operand, straight from global memory (rows past the end re-read the last row)
+    bf16x8 qf[8];
+    {
+        const int qrow = min(q0 + l32, p.Sq - 1);
+        const __bf16 *qp = p.q + ((size_t)((size_t)b * p.Sq + qrow) * p.Hq + head) * HD + 8 * hh;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) qf[s] = *(const bf16x8 *)(qp + 16 * s);
+    }
+    f32x16 acc[4];
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[dt][r] = 0.0f;
+    float m = -INFINITY, l = 0.0f, lr = 0.0f;
+
+    const uint32_t kbase = wave * SPLIT_WAVE_BYTES, vbase = kbase + SPLIT_TILE_BYTES;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
+    // One block = 8 requests of 1 KiB (4 rows): lane L's 16 bytes land at base + 16 L, and the lane
+    // fetches the logical 16-byte unit that the swizzle of the main kernel puts there.
+    auto request = [&](int blk, bool is_v) __attribute__((always_inline)) {
+        const unsigned char *g = uniform_ptr((is_v ? vg : kg) + (size_t)blk * SPLIT_KEYS * kv_row_bytes);
+        const int last = p.Skv - 1 - blk * SPLIT_KEYS;      // rows past the end of K/V re-read the last row
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int row = 4 * i + (lane >> 4);
+            const int unit = lane & 15;
+            const int lu = is_v ? (unit ^ ((row & 3) << 2)) : (unit ^ (row & 15));
+            const uint32_t o = (uint32_t)(min(row, last) * kv_row_bytes) + (lu << 4);
+            lds_dma16(g, o, lds0 + (is_v ? vbase : kbase) + i * 1024);
+        }
+    };
+    int kaddr[8];
+#pragma unroll
+    for (int st = 0; st < 8; ++st) kaddr[st] = kbase + l32 * ROW_BYTES + (((2 * st + hh) ^ (l32 & 15)) << 4);
+    int vaddr[4];
+    {
+        const int i16 = lane & 15, g = (lane >> 4) & 1;
+        const int row = 4 * hh + (i16 >> 2);
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) {
+            const int d = 32 * dt + 16 * g + 4 * (i16 & 3);
+            vaddr[dt] = vbase + row * ROW_BYTES + ((((d >> 3) ^ ((row & 3) << 2))) << 4) + (d & 7) * 2;
+        }
+    }
+
+    // Blocks wave, wave + 8, ...: K(t) and V(t) are requested ahead; K(t + 8) goes out as soon as the
+    // score MFMAs have read K(t), V(t + 8) as soon as the PV MFMAs have read V(t), so that every wait is
+    // "all but the newest eight requests have landed".
+    int t = wave;
+    if (t < nb) {
+        request(t, false);
+        request(t, true);
+    }
+    for (; t < nb; t += NWAVES) {
+        const bool more = t + NWAVES < nb;
+        __builtin_amdgcn_s_waitcnt(wait_vmcnt(8));          // K(t) has landed
+        f32x16 s;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[r] = 0.0f;
+#pragma unroll
+        for (int st = 0; st < 8; ++st) {
+            bf16x8 a = *(const LDS_AS bf16x8 *)(lds + kaddr[st]);
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[st], s, 0, 0, 0);
+        }
+        // (the MFMAs above hold K(t) in registers: the compiler has waited for the LDS reads)
+        __builtin_amdgcn_sched_barrier(0);
+        if (more) request(t + NWAVES, false); else request(t, false);      // same number of requests in flight either way
+        // exact online softmax of the block, masked per key
+        int lim = p.Skv - 1;
+        if (CAUSAL) lim = min(lim, q0 + l32 + off);
+        const int kidx = t * SPLIT_KEYS + 4 * hh;
+        constexpr float NONE = NEG ? INFINITY : -INFINITY;
+        float mx = NONE;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int key = kidx + 8 * (r >> 2) + (r & 3);
+            mx = ext2<NEG>(mx, key <= lim ? s[r] : NONE);
+        }
+        mx = lane32_ext<NEG>(mx);
+        mx = (mx == NONE) ? -INFINITY : mx * p.c;
+        if (__builtin_amdgcn_ballot_w64(mx > m) != 0) {
+            const float mn = fmaxf(m, mx);
+            const float alpha = (mn == -INFINITY) ? 1.0f : __builtin_amdgcn_exp2f(m - mn);
+            m = mn;
+            l *= alpha;
+            lr *= alpha;
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[dt][r] *= alpha;
+        }
+        const float mu = (m == -INFINITY) ? 0.0f : m;
+        uint32_t pb[8];
+        float ls = 0.0f;
+#pragma unroll
+        for (int r = 0; r < 16; r += 2) {
+            const int key = kidx + 8 * (r >> 2) + (r & 3);
+            float e0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], p.c, -mu));
+            float e1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r + 1], p.c, -mu));
+            e0 = (key <= lim) ? e0 : 0.0f;
+            e1 = (key + 1 <= lim) ? e1 : 0.0f;
+            ls += e0 + e1;
+            pb[r >> 1] = pack_bf16(e0, e1);
+            lr = add_bf16_pair(pb[r >> 1], lr);
+        }
+        l += ls;
+        __builtin_amdgcn_s_waitcnt(wait_vmcnt(8));          // V(t) has landed
+#pragma unroll
+        for (int g = 0; g < 2; ++g) {
+            u32x4 pw = {pb[4 * g], pb[4 * g + 1], pb[4 * g + 2], pb[4 * g + 3]};
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt) {
+                const int ro = g * 16 * ROW_BYTES;
+                s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4 *)(lds + vaddr[dt] + ro));
+                s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4 *)(lds + vaddr[dt] + (ro + 8 * ROW_BYTES)));
+                s16x8 av = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av),
+                                                                   __builtin_bit_cast(bf16x8, pw), acc[dt], 0, 0, 0);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (more) request(t + NWAVES, true); else request(t, true);
+    }
+    // nothing of this wavefront's is still on its way into LDS, and its MFMAs have read their operands
+    __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
+
+    // ---- merge.  Each wavefront leaves its accumulator as FP32 [d][query] in its own 16 KiB (its blocks
+    // are dead) and its m, l, lr in the state area; wavefront w then combines d = 16 w .. 16 w + 15.
+    {
+        LDS_AS float *part = (LDS_AS float *)(lds + wave * SPLIT_WAVE_BYTES);
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int d = 32 * dt + 8 * (r >> 2) + 4 * hh + (r & 3);
+                part[d * 32 + l32] = acc[dt][r];
+            }
+        // every lane of a query holds the same m; l and lr are the lane's share: add the two halves
+        const float lt = lane32_sum(l), lrt = lane32_sum(lr);
+        LDS_AS float *state = (LDS_AS float *)(lds + SPLIT_STATE_BASE) + wave * 96;
+        if (hh == 0) {
+            state[l32] = m;
+            state[32 + l32] = lt;
+            state[64 + l32] = lrt;
+        }
+    }
+    __syncthreads();
+    {
+        const LDS_AS float *state = (const LDS_AS float *)(lds + SPLIT_STATE_BASE);
+        float mw[NWAVES], M = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < NWAVES; ++w) {
+            mw[w] = state[w * 96 + l32];
+            M = fmaxf(M, mw[w]);
+        }
+        float L = 0.0f, LR = 0.0f, o8[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) o8[j] = 0.0f;
+#pragma unroll
+        for (int w = 0; w < NWAVES; ++w) {
+            const float f = (mw[w] == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(mw[w] - M);
+            L += f * state[w * 96 + 32 + l32];
+            LR += f * state[w * 96 + 64 + l32];
+            const LDS_AS float *part = (const LDS_AS float *)(lds + w * SPLIT_WAVE_BYTES);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) o8[j] += f * part[(16 * wave + 8 * hh + j) * 32 + l32];
+        }
+        const float inv = LR > 0.0f ? 1.0f / LR : 0.0f;
+        if (q0 + l32 < p.Sq) {
+            u32x4 ww = {pack_bf16(o8[0] * inv, o8[1] * inv), pack_bf16(o8[2] * inv, o8[3] * inv),
+                        pack_bf16(o8[4] * inv, o8[5] * inv), pack_bf16(o8[6] * inv, o8[7] * inv)};
+            __bf16 *op = p.o + ((size_t)((size_t)b * p.Sq + q0 + l32) * p.Hq + head) * HD + 16 * wave + 8 * hh;
+            *(u32x4 *)op = ww;
+            if (wave == 0 && hh == 0)
+                p.lse[((size_t)b * p.Hq + head) * p.Sq + q0 + l32] =
+                    L > 0.0f ? (M + __builtin_amdgcn_logf(L)) * 0.6931471805599453f : -INFINITY;
+        }
+    }
+}
+
 }  // namespace
 
 extern "C" {
@@ -1079,12 +1313,46 @@ int attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
             hipFuncSetAttribute((const void *)attn_fwd_kernel<true, true>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess ||
             hipFuncSetAttribute((const void *)attn_fwd_kernel<false, true>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess)
+                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess ||
+            hipFuncSetAttribute((const void *)attn_fwd_split_kernel<true, false>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, SPLIT_LDS_BYTES) != hipSuccess ||
+            hipFuncSetAttribute((const void *)attn_fwd_split_kernel<false, false>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, SPLIT_LDS_BYTES) != hipSuccess ||
+            hipFuncSetAttribute((const void *)attn_fwd_split_kernel<true, true>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, SPLIT_LDS_BYTES) != hipSuccess ||
+            hipFuncSetAttribute((const void *)attn_fwd_split_kernel<false, true>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, SPLIT_LDS_BYTES) != hipSuccess)
             return ATTN_E_LAUNCH;
         cus[dev].store(n, std::memory_order_release);
     }
-    // One workgroup per CU (a workgroup takes all of a CU's registers and LDS), each working through a list.
     const int ncu = cus[dev].load(std::memory_order_relaxed);
+    hipStream_t st = (hipStream_t)stream;
+    // a negative scale turns the running maximum of the scaled scores into c times the smallest raw score
+    const bool neg = scale < 0.0f;
+
+    // Small problems: few 256-row items would leave most compute units idle; 32-row items whose keys
+    // are shared out among the wavefronts of a workgroup fill the device instead.
+    const int64_t split_items = (int64_t)B * Hq * ((Sq + 31) / 32);
+    const bool small = ATTN_SMALL_PATH == 2 || (ATTN_SMALL_PATH == 1 && total * 4 <= ncu);
+    if (small && split_items < INT32_MAX) {
+        SplitParams sp = {};
+        sp.q = p.q; sp.k = p.k; sp.v = p.v; sp.o = p.o; sp.lse = lse;
+        sp.Hq = Hq; sp.Hkv = Hkv; sp.Sq = Sq; sp.Skv = Skv; sp.G = sh.G;
+        sp.ntile = (Sq + 31) / 32;
+        sp.c = p.c;
+        const dim3 sgrid((unsigned)split_items), sblock(NTHREADS);
+        if (causal && neg)
+            hipLaunchKernelGGL((attn_fwd_split_kernel<true, true>), sgrid, sblock, SPLIT_LDS_BYTES, st, sp);
+        else if (causal)
+            hipLaunchKernelGGL((attn_fwd_split_kernel<true, false>), sgrid, sblock, SPLIT_LDS_BYTES, st, sp);
+        else if (neg)
+            hipLaunchKernelGGL((attn_fwd_split_kernel<false, true>), sgrid, sblock, SPLIT_LDS_BYTES, st, sp);
+        else
+            hipLaunchKernelGGL((attn_fwd_split_kernel<false, false>), sgrid, sblock, SPLIT_LDS_BYTES, st, sp);
+        return hipGetLastError() == hipSuccess ? ATTN_OK : ATTN_E_LAUNCH;
+    }
+
+    // One workgroup per CU (a workgroup takes all of a CU's registers and LDS), each working through a list.
     const int cu_slots = ncu >= 8 ? ncu / 8 : 1;
     sc.per_xcd = (int)((total + 7) / 8);
     sc.split = sc.nsub = sc.sgx = sc.window = 1;
@@ -1103,9 +1371,6 @@ int attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
     sc.d_window = make_div((uint32_t)sc.window);
     sc.slots = sc.per_xcd < cu_slots ? sc.per_xcd : cu_slots;
     const dim3 grid((unsigned)(sc.slots * 8)), block(NTHREADS);
-    hipStream_t st = (hipStream_t)stream;
-    // a negative scale turns the running maximum of the scaled scores into c times the smallest raw score
-    const bool neg = scale < 0.0f;
     if (causal && neg)
         hipLaunchKernelGGL((attn_fwd_kernel<true, true>), grid, block, LDS_BYTES, st, p);
     else if (causal)

@@ -15,8 +15,8 @@ LIBS = [("shipped", B.LIB)] + [(n, B.variant_path(n)) for n in B.VARIANTS]
 @pytest.mark.parametrize("name,path", LIBS, ids=[n for n, _ in LIBS])
 def test_attention_kernels_have_no_scratch_and_fit_the_register_file(name, path):
     meta = codeobj.kernel_metadata(path)
-    kernels = {k: v for k, v in meta.items() if "attn_fwd_kernel" in k}
-    assert len(kernels) == 4, sorted(meta)          # causal x sign of the scale
+    kernels = {k: v for k, v in meta.items() if "attn_fwd_kernel" in k or "attn_fwd_split_kernel" in k}
+    assert len(kernels) == 8 and len(meta) == 8, sorted(meta)       # two kernels x causal x sign of the scale
     for k, f in kernels.items():
         assert f["private_segment_fixed_size"] == 0, (name, k, f)
         assert f["vgpr_spill_count"] == 0, (name, k, f)

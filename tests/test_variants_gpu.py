@@ -28,6 +28,54 @@ def _entry(name):
     return lambda *a: P.variant_attn_fwd(name, *a)
 
 
+# The shipped library sends launches with few 256-row work items to the split-key kernel, which would
+# leave the small shapes of the parity tests to that kernel alone: the two builds below pin the choice,
+# so that BOTH kernels see every small and ragged shape (and the split-key kernel some larger ones).
+import test_attn_gpu as T     # noqa: E402
+
+
+@pytest.mark.parametrize("causal", [False, True], ids=["full", "causal"])
+@pytest.mark.parametrize("shape", T.SHAPES, ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("name", ["no_small_path", "always_small_path"])
+def test_both_kernels_on_small_shapes(name, shape, causal):
+    Bn, Hq, Hkv, Sq, Skv = shape
+    q, k, v = U.rand_qkv(Bn, Hq, Hkv, Sq, Skv, seed=hash(shape) % 10000)
+    print(f"variant {name} shape={shape} causal={causal}", flush=True)
+    U.check_full(q, k, v, causal, SCALE, what=f"{name} {shape} causal={causal}", attn_fwd=_entry(name))
+
+
+@pytest.mark.parametrize("name", ["no_small_path", "always_small_path"])
+def test_both_kernels_on_random_shapes_and_hard_cases(name):
+    rng = np.random.default_rng(20260325)
+    for n in range(24):
+        hkv = int(rng.choice([1, 2, 3, 5]))
+        g = int(rng.choice([1, 2, 3, 4, 6, 8, 16]))
+        Bn = int(rng.integers(1, 4))
+        Sq = int(rng.integers(1, 700))
+        Skv = int(rng.integers(1, 900))
+        causal = bool(rng.integers(0, 2))
+        q_mul = float(rng.choice([1.0, 1.0, 4.0]))
+        print(f"variant {name} case {n}: B={Bn} Hq={hkv * g} Hkv={hkv} Sq={Sq} Skv={Skv} causal={causal} q_mul={q_mul}", flush=True)
+        q, k, v = U.rand_qkv(Bn, hkv * g, hkv, Sq, Skv, seed=3000 + n, q_mul=q_mul)
+        U.check_full(q, k, v, causal, SCALE, what=f"{name} random case {n}", attn_fwd=_entry(name))
+    # rows without keys, huge scores, negative scale, keys that dominate
+    q, k, v = U.rand_qkv(1, 2, 2, 300, 40, seed=3)
+    U.check_full(q, k, v, True, SCALE, what=f"{name} empty rows", attn_fwd=_entry(name))
+    q, k, v = U.rand_qkv(1, 2, 2, 640, 1024, seed=33, q_mul=64.0)
+    U.check_full(q, k, v, False, 1.0, what=f"{name} huge scores", attn_fwd=_entry(name))
+    U.check_full(q, k, v, True, -1.0, what=f"{name} huge scores, negative scale", attn_fwd=_entry(name))
+    q, _, v = U.rand_qkv(2, 4, 4, 500, 500, seed=34, q_mul=1.5)
+    U.check_full(q, q.clone(), v, True, SCALE, what=f"{name} K = Q", attn_fwd=_entry(name))
+
+
+def test_split_kernel_long_keys_few_rows():
+    """What the split-key kernel is for: a handful of query rows against a long key sequence."""
+    for (Bn, Hq, Hkv, Sq, Skv, causal) in [(1, 8, 2, 1, 20000, False), (2, 4, 4, 17, 9001, True), (1, 32, 8, 64, 4096, True)]:
+        q, k, v = U.rand_qkv(Bn, Hq, Hkv, Sq, Skv, seed=4400 + Sq)
+        print(f"shape {(Bn, Hq, Hkv, Sq, Skv)} causal={causal}", flush=True)
+        U.check_full(q, k, v, causal, SCALE, what=f"long keys {(Bn, Hq, Hkv, Sq, Skv)}")
+
+
 @pytest.mark.parametrize("causal", [False, True], ids=["full", "causal"])
 @pytest.mark.parametrize("name", sorted(B.VARIANTS))
 def test_variant_parity_small_shapes(name, causal):
