@@ -1098,16 +1098,27 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_split_kernel(const SplitPar
     const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
     // One block = 8 requests of 1 KiB (4 rows): lane L's 16 bytes land at base + 16 L, and the lane
     // fetches the logical 16-byte unit that the swizzle of the main kernel puts there.
+    uint32_t koff[8], voff[8];      // byte offset of this lane's 16 bytes from the first row of a full block
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int row = 4 * i + (lane >> 4), unit = lane & 15;
+        koff[i] = (uint32_t)(row * kv_row_bytes) + ((unit ^ (row & 15)) << 4);
+        voff[i] = (uint32_t)(row * kv_row_bytes) + ((unit ^ ((row & 3) << 2)) << 4);
+    }
     auto request = [&](int blk, bool is_v) __attribute__((always_inline)) {
         const unsigned char *g = uniform_ptr((is_v ? vg : kg) + (size_t)blk * SPLIT_KEYS * kv_row_bytes);
         const int last = p.Skv - 1 - blk * SPLIT_KEYS;      // rows past the end of K/V re-read the last row
+        const uint32_t dst = lds0 + (is_v ? vbase : kbase);
+        if (last >= SPLIT_KEYS - 1) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int row = 4 * i + (lane >> 4);
-            const int unit = lane & 15;
-            const int lu = is_v ? (unit ^ ((row & 3) << 2)) : (unit ^ (row & 15));
-            const uint32_t o = (uint32_t)(min(row, last) * kv_row_bytes) + (lu << 4);
-            lds_dma16(g, o, lds0 + (is_v ? vbase : kbase) + i * 1024);
+            for (int i = 0; i < 8; ++i) lds_dma16(g, is_v ? voff[i] : koff[i], dst + i * 1024);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int row = 4 * i + (lane >> 4);
+                const uint32_t o = (is_v ? voff[i] : koff[i]) - (uint32_t)(row * kv_row_bytes) + (uint32_t)(min(row, last) * kv_row_bytes);
+                lds_dma16(g, o, dst + i * 1024);
+            }
         }
     };
     int kaddr[8];
@@ -1125,8 +1136,8 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_split_kernel(const SplitPar
     }
 
     // Blocks wave, wave + 8, ...: K(t) and V(t) are requested ahead; K(t + 8) goes out as soon as the
-    // score MFMAs have read K(t), V(t + 8) as soon as the PV MFMAs have read V(t), so that every wait is
-    // "all but the newest eight requests have landed".
+    // score MFMAs have read K(t), V(t + 8) as soon as the PV MFMAs have read V(t), so that a wait is "all
+    // but the newest eight requests have landed" while there is a next block and "all" at the last one.
     int t = wave;
     if (t < nb) {
         request(t, false);
@@ -1145,7 +1156,7 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_split_kernel(const SplitPar
         }
         // (the MFMAs above hold K(t) in registers: the compiler has waited for the LDS reads)
         __builtin_amdgcn_sched_barrier(0);
-        if (more) request(t + NWAVES, false); else request(t, false);      // same number of requests in flight either way
+        if (more) request(t + NWAVES, false);
         // exact online softmax of the block, masked per key
         int lim = p.Skv - 1;
         if (CAUSAL) lim = min(lim, q0 + l32 + off);
@@ -1185,7 +1196,8 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_split_kernel(const SplitPar
             lr = add_bf16_pair(pb[r >> 1], lr);
         }
         l += ls;
-        __builtin_amdgcn_s_waitcnt(wait_vmcnt(8));          // V(t) has landed
+        // V(t) has landed: behind it in the queue are the requests of K(t + 8), if there is such a block
+        if (more) __builtin_amdgcn_s_waitcnt(wait_vmcnt(8)); else __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
 #pragma unroll
         for (int g = 0; g < 2; ++g) {
             u32x4 pw = {pb[4 * g], pb[4 * g + 1], pb[4 * g + 2], pb[4 * g + 3]};
@@ -1200,21 +1212,26 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_split_kernel(const SplitPar
             }
         }
         __builtin_amdgcn_sched_barrier(0);
-        if (more) request(t + NWAVES, true); else request(t, true);
+        if (more) request(t + NWAVES, true);
     }
-    // nothing of this wavefront's is still on its way into LDS, and its MFMAs have read their operands
+    // nothing of this wavefront's is still on its way into LDS (the last block waited for everything),
+    // and its MFMAs have read their operands
     __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
 
-    // ---- merge.  Each wavefront leaves its accumulator as FP32 [d][query] in its own 16 KiB (its blocks
-    // are dead) and its m, l, lr in the state area; wavefront w then combines d = 16 w .. 16 w + 15.
+    // ---- merge.  Each wavefront leaves its accumulator as FP32 [query][d] in its own 16 KiB (its blocks
+    // are dead), the 16-byte units of a query's row swizzled by the query so that the 32 lanes of a
+    // store or load touch 32 different units, and its m, l, lr in the state area; wavefront w then
+    // combines d = 16 w .. 16 w + 15.
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
     {
-        LDS_AS float *part = (LDS_AS float *)(lds + wave * SPLIT_WAVE_BYTES);
+        LDS_AS unsigned char *part = lds + wave * SPLIT_WAVE_BYTES + l32 * (HD * 4);
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int d = 32 * dt + 8 * (r >> 2) + 4 * hh + (r & 3);
-                part[d * 32 + l32] = acc[dt][r];
+            for (int rg = 0; rg < 4; ++rg) {
+                const int u = 8 * dt + 2 * rg + hh;          // d = 4 u .. 4 u + 3
+                const f32x4 val = {acc[dt][4 * rg], acc[dt][4 * rg + 1], acc[dt][4 * rg + 2], acc[dt][4 * rg + 3]};
+                *(LDS_AS f32x4 *)(part + ((u ^ l32) << 4)) = val;
             }
         // every lane of a query holds the same m; l and lr are the lane's share: add the two halves
         const float lt = lane32_sum(l), lrt = lane32_sum(lr);
@@ -1242,9 +1259,15 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_split_kernel(const SplitPar
             const float f = (mw[w] == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(mw[w] - M);
             L += f * state[w * 96 + 32 + l32];
             LR += f * state[w * 96 + 64 + l32];
-            const LDS_AS float *part = (const LDS_AS float *)(lds + w * SPLIT_WAVE_BYTES);
+            const LDS_AS unsigned char *part = lds + w * SPLIT_WAVE_BYTES + l32 * (HD * 4);
+            const int u = 4 * wave + 2 * hh;
+            const f32x4 lo = *(const LDS_AS f32x4 *)(part + ((u ^ l32) << 4));
+            const f32x4 hi = *(const LDS_AS f32x4 *)(part + (((u + 1) ^ l32) << 4));
 #pragma unroll
-            for (int j = 0; j < 8; ++j) o8[j] += f * part[(16 * wave + 8 * hh + j) * 32 + l32];
+            for (int j = 0; j < 4; ++j) {
+                o8[j] += f * lo[j];
+                o8[4 + j] += f * hi[j];
+            }
         }
         const float inv = LR > 0.0f ? 1.0f / LR : 0.0f;
         if (q0 + l32 < p.Sq) {
