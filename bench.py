@@ -42,7 +42,8 @@ def mfma_probe():
     sink = torch.zeros(1, dtype=torch.float32, device=dev)
     clocks = torch.zeros(4, dtype=torch.int64, device=dev)
     g = torch.Generator().manual_seed(7)
-    tiles = torch.randn(1 << 24, generator=g).to(torch.bfloat16).to(dev)         # 32 MiB of N(0,1) BF16
+    # 4 MiB of N(0,1) BF16 for the tile requests: like the attention kernel's K/V tiles, mostly served by L2
+    tiles = torch.randn(1 << 21, generator=g).to(torch.bfloat16).to(dev)
     data = {"zeros": torch.zeros(12, 64, 8), "normal_0_1": torch.randn(12, 64, 8, generator=g)}
 
     def run(ops, mode, waves):
@@ -78,9 +79,10 @@ def mfma_probe():
     return out
 
 
-def kernel_clock(w, qd, kd, vd, o, lse, launches=10):
+def kernel_clock(w, qd, kd, vd, o, lse, launches=40):
     """Shader clock and cycle count of the attention kernel on this workload: the build of the shipped kernel
-    with clock stamps (variants/libattn_clocks.so), launched back to back like the timed run."""
+    with clock stamps (variants/libattn_clocks.so), launched back to back like the timed run (the stamps are
+    those of the last launch, when the board has settled at the clock this load allows)."""
     from paper_2603_24517_amd import probe as P
     stream = torch.cuda.current_stream()
     for _ in range(launches):
