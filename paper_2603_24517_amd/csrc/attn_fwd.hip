@@ -82,6 +82,13 @@
 #ifndef ATTN_LDS_PREFETCH
 #define ATTN_LDS_PREFETCH 3
 #endif
+// ATTN_WAVES_PER_SIMD (shipped: 2): the occupancy the attention kernel is compiled for, i.e. its register
+// budget: 512 / n vector registers per wavefront.  3 and 4 are for compile-only builds that show what a
+// smaller budget costs in spills (the paper's section 5.3 weighs register budgets on its hardware);
+// a build that spills must not be run, see wait_vmcnt below.
+#ifndef ATTN_WAVES_PER_SIMD
+#define ATTN_WAVES_PER_SIMD 2
+#endif
 // ATTN_CLOCKS (undefined in the shipped library): the first wavefront of the first workgroup stamps the
 // shader cycle counter and the constant 100 MHz counter when it starts and when it ends, and the
 // library exports attn_clocks_read(); the benchmark derives the shader clock of a launch from them.
@@ -260,7 +267,8 @@ __device__ unsigned long long g_clocks[4];      // cycle counter at start / end,
 #endif
 
 template <bool CAUSAL, bool NEG>
-__global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_fwd_kernel(const Params p)
+__global__ __launch_bounds__(NTHREADS) __attribute__((amdgpu_waves_per_eu(ATTN_WAVES_PER_SIMD, ATTN_WAVES_PER_SIMD)))
+void attn_fwd_kernel(const Params p)
 {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     LDS_AS unsigned char *lds = (LDS_AS unsigned char *)smem;
