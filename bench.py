@@ -79,6 +79,15 @@ def mfma_probe():
     return out
 
 
+def kernel_name(w, compute_units):
+    """Which of the library's two kernels a launch of this workload runs (the rule of include/attn.h: the
+    split-key kernel when the 256-row work items would occupy at most a quarter of the compute units)."""
+    g = w.Hq // w.Hkv
+    pack = 8 if g % 8 == 0 else 4 if g % 4 == 0 else 2 if g % 2 == 0 else 1
+    items = w.B * w.Hkv * (g // pack) * -(-w.Sq // (256 // pack))
+    return "attn_fwd_split_kernel" if items * 4 <= compute_units else "attn_fwd_kernel"
+
+
 def kernel_clock(w, qd, kd, vd, o, lse, launches=40):
     """Shader clock and cycle count of the attention kernel on this workload: the build of the shipped kernel
     with clock stamps (variants/libattn_clocks.so), launched back to back like the timed run (the stamps are
@@ -90,8 +99,7 @@ def kernel_clock(w, qd, kd, vd, o, lse, launches=40):
                                 stream.cuda_stream)
         if rc != 0:
             raise A.AttnError(rc)
-    cycles, ghz = P.clocks_read()
-    return {"cycles_first_workgroup": int(cycles), "clock_ghz": ghz}
+    return P.clocks_read()
 
 
 TRAFFIC_FILE = "profiles/attn_fwd_kernel_hbm_traffic.md"
@@ -194,6 +202,8 @@ def run_workload(name, steps, warmup, with_cpu, repeats=1, variant=None):
     tflops = w.flops / (ms * 1e-3) * 1e-12
     ktflops = w.flops / (kms * 1e-3) * 1e-12
     traffic, traffic_source = traffic_from_profiles(w.name)
+    from paper_2603_24517_amd import probe as P
+    rc, cus, khz = P.attn_probe_device_info()
     out = {
         "metric": METRIC, "value": tflops, "unit": "TFLOPS", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -204,11 +214,9 @@ def run_workload(name, steps, warmup, with_cpu, repeats=1, variant=None):
                    "flops_per_step": w.flops},
         "roofline": {"bound": "mfma", "achieved": ktflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": ktflops / PEAK_BF16_TFLOPS, "traffic": traffic, "traffic_source": traffic_source,
-                     "kernel": "attn_fwd_kernel", "kernel_ms": kms,
+                     "kernel": kernel_name(w, cus), "kernel_ms": kms,
                      "algorithmic_bytes": w.algorithmic_bytes},
     }
-    from paper_2603_24517_amd import probe as P
-    rc, cus, khz = P.attn_probe_device_info()
     out["device"] = {"name": torch.cuda.get_device_properties(0).name, "compute_units": cus if rc == 0 else None,
                      "max_clock_mhz": khz / 1e3 if rc == 0 else None,
                      "peak_note": "2516.6 = 256 CU x 4 SIMD x 1024 FLOP/clk x 2.4 GHz"}

@@ -54,11 +54,16 @@ enum {
  * Size limits (ATTN_E_UNSUPPORTED beyond them): Sq + Skv below 2^31 - 1024,
  * Hq and Hkv at most 32768, and fewer than 2^27 work items, one item being 256/p query rows of p query
  * heads that share a K/V head (p = 8, 4, 2 or 1, the largest that divides
- * Hq / Hkv).  The launch uses one workgroup per compute unit of the current
- * device (all of its LDS); the first call on a device queries the device once
- * and sets a function attribute, so make one ordinary call on a device before
- * recording attn_fwd into a HIP graph (later calls are one kernel launch and
- * nothing else, and replay correctly).
+ * Hq / Hkv).  The launch is one kernel: with one workgroup per compute unit of
+ * the current device (all of its LDS), each working through a list of such
+ * items -- or, when those items would occupy at most a quarter of the compute
+ * units (few query rows, however long the key sequence), with one workgroup per
+ * 32 query rows of one query head, whose wavefronts share the item's keys and
+ * merge their partial results through LDS.  Either way nothing is allocated.
+ * The first call on a device queries the device once and sets function
+ * attributes, so make one ordinary call on a device before recording attn_fwd
+ * into a HIP graph (later calls are one kernel launch and nothing else, and
+ * replay correctly).
  *
  * Inputs and outputs must not overlap and must stay alive until the stream
  * reaches the end of the kernel.  The call only enqueues work.  Every

@@ -62,11 +62,16 @@ int attn_probe_device_info(int *compute_units, int *clock_khz);
 
 /*
  * attn_clocks_read -- exported only by the build of the ATTENTION library with -DATTN_CLOCKS
- * (paper_2603_24517_amd/variants/libattn_clocks.so: the shipped kernel plus four stamps), not by
+ * (paper_2603_24517_amd/variants/libattn_clocks.so: the shipped kernels plus these stamps), not by
  * libattn_probe.so.  Waits for the device, then copies the stamps that the first wavefront of the
- * first workgroup of the last attn_fwd launch took: shader cycle counter at its start and end, then
- * the constant 100 MHz counter at its start and end.
- *   out  out  host, 4 x 64-bit
+ * first workgroup of the last attn_fwd launch took:
+ *   out[0], out[1]  shader cycle counter at its start and at its end
+ *   out[2], out[3]  the constant 100 MHz counter at its start and at its end
+ *   out[4..6]       256-row kernel only, second work item of that workgroup: cycle counter where its
+ *                   key-block loop starts (first two score products and first softmax done) and where
+ *                   it ends (last barrier passed), and the number of iterations in between
+ *   out[7..9]       the same for its third work item (stale or zero if the workgroup had fewer items)
+ *   out  out  host, 10 x 64-bit
  * Returns 0, or a negative ATTN_E_* code of include/attn.h.
  */
 int attn_clocks_read(unsigned long long *out);

@@ -43,6 +43,11 @@
 // the instruction stream as far as possible, because with two wavefronts per
 // SIMD the issue of vector instructions, not the matrix pipe alone, is what
 // an iteration's length follows.
+//
+// A second kernel at the end of this file serves small problems (few query
+// rows, however many keys): 32-row work items whose key blocks are shared out
+// among the wavefronts of a workgroup and whose partial results are merged
+// through LDS.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <math.h>
@@ -90,8 +95,10 @@
 #define ATTN_WAVES_PER_SIMD 2
 #endif
 // ATTN_CLOCKS (undefined in the shipped library): the first wavefront of the first workgroup stamps the
-// shader cycle counter and the constant 100 MHz counter when it starts and when it ends, and the
-// library exports attn_clocks_read(); the benchmark derives the shader clock of a launch from them.
+// shader cycle counter and the constant 100 MHz counter when it starts and when it ends, and the cycle
+// counter where the key-block loop of its second and of its third work item starts and ends; the
+// library exports attn_clocks_read(), and the benchmark derives the shader clock of a launch, the
+// length of an iteration and the stretch between two items from the stamps.
 static_assert(ATTN_SOFTMAX >= 0 && ATTN_SOFTMAX <= 3, "ATTN_SOFTMAX is 0, 1, 2 or 3");
 static_assert(ATTN_LDS_PREFETCH >= 1 && ATTN_LDS_PREFETCH <= 8, "ATTN_LDS_PREFETCH is 1 .. 8");
 
@@ -263,7 +270,13 @@ __device__ __forceinline__ void wg_barrier() {
 }
 
 #ifdef ATTN_CLOCKS
-__device__ unsigned long long g_clocks[4];      // cycle counter at start / end, 100 MHz counter at start / end
+// cycle counter at start / end, 100 MHz counter at start / end; then, for the second and the third item of
+// the first workgroup: cycle counter at the start and at the end of the key-block loop, and the loop's iterations
+__device__ unsigned long long g_clocks[10];
+#define ATTN_STAMP(k, v) do { __builtin_amdgcn_sched_barrier(0); if (bid == 0 && tid == 0 && (item_no == 1 || item_no == 2)) \
+                                  g_clocks[4 + 3 * (item_no - 1) + (k)] = (v); __builtin_amdgcn_sched_barrier(0); } while (0)
+#else
+#define ATTN_STAMP(k, v) do { } while (0)
 #endif
 
 template <bool CAUSAL, bool NEG>
@@ -819,6 +832,9 @@ void attn_fwd_kernel(const Params p)
         load_q(cur);
     }
     bool warm = false;          // the first tiles of the item about to start were requested by the item before it
+#ifdef ATTN_CLOCKS
+    int item_no = 0;
+#endif
     while (have) {
         enter(cur);
         reset_state();
@@ -875,6 +891,7 @@ void attn_fwd_kernel(const Params p)
             // branch around the MFMA sequences.  Iteration j: scur = S(j+1) (sb for even j), snxt
             // receives S(j+2).
             int j = 0;
+            ATTN_STAMP(0, __builtin_readcyclecounter());
             // Iterations j < fast_end take the fast path: S(j+1) needs no mask, and the tiles requested are
             // full ones (past the last block: of the next item, or the last block again).
             int fast_end = all_full ? n_unm - 1 : min(n_unm - 1, nfull - (2 + REQ_AHEAD));
@@ -966,6 +983,8 @@ void attn_fwd_kernel(const Params p)
             // the last iteration has only its PV product left to do
             if (nblk - 1 < n_w) pv_only(stage_off(nblk - 1));
             iteration_end(nblk - 1);
+            ATTN_STAMP(1, __builtin_readcyclecounter());
+            ATTN_STAMP(2, (unsigned long long)nblk);
         }
         // Nothing may still be writing LDS at exit; the next item's Q has landed; and its K'(2), V'(0) are
         // waited for here, before the epilogue's stores join the queue, so that its first barrier can
@@ -1028,6 +1047,9 @@ void attn_fwd_kernel(const Params p)
         }
 
         if (!ATTN_ITEM_OVERLAP && have2) load_q(nxt);
+#ifdef ATTN_CLOCKS
+        ++item_no;
+#endif
         ring0 = (ring0 + nblk) % NSTAGE;
         warm = warm_next;
         have = have2;
@@ -1074,6 +1096,9 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_split_kernel(const SplitPar
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, hh = lane >> 5;
     const int item = blockIdx.x;
+#ifdef ATTN_CLOCKS
+    if (item == 0 && tid == 0) { g_clocks[2] = wall_clock64(); g_clocks[0] = __builtin_readcyclecounter(); }
+#endif
     const int tile = item % p.ntile, bh = item / p.ntile;
     const int head = bh % p.Hq, b = bh / p.Hq;
     const int hkv = head / p.G;
@@ -1288,6 +1313,9 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_split_kernel(const SplitPar
                     L > 0.0f ? (M + __builtin_amdgcn_logf(L)) * 0.6931471805599453f : -INFINITY;
         }
     }
+#ifdef ATTN_CLOCKS
+    if (item == 0 && tid == 0) { g_clocks[1] = __builtin_readcyclecounter(); g_clocks[3] = wall_clock64(); }
+#endif
 }
 
 }  // namespace
@@ -1430,7 +1458,7 @@ const char *attn_strerror(int code)
 int attn_version(void) { return 1001; }
 
 #ifdef ATTN_CLOCKS
-// Waits for the device, then copies the stamps of the last launch to the host (4 x 64-bit).
+// Waits for the device, then copies the stamps of the last launch to the host (10 x 64-bit).
 int attn_clocks_read(unsigned long long *out)
 {
     if (!out) return ATTN_E_NULL;

@@ -73,10 +73,18 @@ def variant_attn_fwd(name, q, k, v, o, lse, B, Hq, Hkv, Sq, Skv, D, causal, scal
 
 
 def clocks_read():
-    """Stamps of the last launch of the `clocks` variant: (cycles, GHz).  Waits for the device."""
-    out = (ctypes.c_ulonglong * 4)()
+    """Stamps of the last launch of the `clocks` variant, as a dict: cycles and clock of the first workgroup,
+    and (256-row kernel, a workgroup with at least three items) the cycles per key-block iteration of its
+    third item and the cycles between the loops of its second and third item.  Waits for the device."""
+    out = (ctypes.c_ulonglong * 10)()
     rc = load_variant("clocks").attn_clocks_read(out)
     if rc != 0:
         raise RuntimeError(f"attn_clocks_read failed ({rc})")
     cycles, ticks = out[1] - out[0], out[3] - out[2]
-    return cycles, (0.1 * cycles / ticks if ticks else float("nan"))
+    res = {"cycles_first_workgroup": int(cycles), "clock_ghz": (0.1 * cycles / ticks) if ticks else None}
+    s2, e2, n2, s3, e3, n3 = (int(out[i]) for i in range(4, 10))
+    if out[0] <= s2 < e2 <= s3 < e3 <= out[1] and n3 > 0:     # stamps of this launch, in order
+        res["cycles_per_iteration"] = (e3 - s3) / n3
+        res["cycles_between_items"] = s3 - e2
+        res["iterations_per_item"] = n3
+    return res

@@ -119,9 +119,12 @@ def test_clocks_variant_reports_a_plausible_clock():
     for _ in range(3):
         assert P.variant_attn_fwd("clocks", q, k, v, o, lse, w.B, w.Hq, w.Hkv, w.Sq, w.Skv, w.D, False, w.scale,
                                   torch.cuda.current_stream().cuda_stream) == 0
-    cycles, ghz = P.clocks_read()
-    print(f"cycles {cycles}, clock {ghz:.3f} GHz", flush=True)
-    assert 5e5 < cycles < 5e6 and 0.5 < ghz < 2.6
+    c = P.clocks_read()
+    print(c, flush=True)
+    assert 5e5 < c["cycles_first_workgroup"] < 5e6 and 0.5 < c["clock_ghz"] < 2.6
+    # 8 items of 64 key blocks per workgroup: an iteration is at least the 2048 matrix-pipe cycles of its MFMAs
+    assert c["iterations_per_item"] == 64 and 2048 <= c["cycles_per_iteration"] < 6000
+    assert 1000 < c["cycles_between_items"] < 60000
 
 
 @pytest.mark.parametrize("waves", [1, 2, 4])
