@@ -90,7 +90,7 @@
 // ATTN_WAVES_PER_SIMD (shipped: 2): the occupancy the attention kernel is compiled for, i.e. its register
 // budget: 512 / n vector registers per wavefront.  3 and 4 are for compile-only builds that show what a
 // smaller budget costs in spills (the paper's section 5.3 weighs register budgets on its hardware);
-// a build that spills must not be run, see wait_vmcnt below.
+// such builds are not meant to be run (see wait_vmcnt below for what a spill costs in this loop).
 #ifndef ATTN_WAVES_PER_SIMD
 #define ATTN_WAVES_PER_SIMD 2
 #endif
@@ -135,12 +135,13 @@ constexpr float P_SUM_LIMIT = 16384.0f;
 constexpr int MAT_PREFETCH = ATTN_LDS_PREFETCH;   // LDS reads run this many MFMAs ahead of their consumer
 // s_waitcnt vmcnt(n), n < 16, other counters untouched.  The tile requests are counted by hand: "all but
 // the newest n vector-memory operations have completed" stands for "the tiles of the iterations before
-// have landed" only while the requests are the only loads in the queue around them.  Loads complete in
-// order among themselves, but stores are not ordered with them, so a register spill (scratch stores and
-// loads of the compiler's own) between two requests would let the count fall to n while an older tile
-// load is still under way: the kernels must compile without scratch (a host-side test of the built code
-// object checks that), and the epilogue's stores are issued only after the wait that the next item's
-// first tiles need.
+// have landed".  That holds whatever else is in the queue, because the loads that must have landed are
+// always followed by n newer loads and loads complete in order; but it is only CHEAP while the requests
+// are the only memory operations of the loop: a register spill would bring reloads of the compiler's own,
+// each behind an s_waitcnt vmcnt(0) that waits for every tile request in flight (a memory latency per
+// reload, in a loop whose iteration is shorter than one).  So the kernels must compile without scratch
+// (a host-side test of the built code object checks that), and the epilogue's stores are issued only
+// after the wait that the next item's first tiles need.
 constexpr int wait_vmcnt(int n) { return 0x0F70 | n; }
 constexpr int WAIT_VMCNT0 = wait_vmcnt(0);
 // end of an iteration: everything but the loads of the last REQ_AHEAD-1 iterations has landed

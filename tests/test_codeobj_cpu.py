@@ -1,9 +1,9 @@
 """The built code objects keep every kernel inside the register file and out of scratch memory.
 
 The key-block loop counts its own outstanding tile loads (s_waitcnt vmcnt(n) written by hand); a
-register spill would put loads and stores of the compiler's own into that count, so "no scratch, no
-spilled vector register" is a correctness condition of the shipped library and of every variant that
-the GPU tests run, not only a performance wish.  Read from the metadata notes of the code object."""
+register spill would put reloads of the compiler's own into that loop, each behind a wait for every
+tile request in flight, so "no scratch, no spilled vector register" is a rule of the shipped library
+and of every variant that the GPU tests run.  Read from the metadata notes of the code object."""
 import pytest
 
 from paper_2603_24517_amd import build as B
