@@ -114,7 +114,7 @@ def traffic_from_profiles(name):
         return None, None
     text = open(path).read()
     m = re.search(r"traffic_bytes_per_launch\[%s\]\s*=\s*(\d+)" % re.escape(name), text)
-    c = re.search(r"kernel source at commit\s+`?([0-9a-f]{7,40})", text)
+    c = re.search(r"kernel source at commit\s+`?([0-9a-f]{7,40})", text, flags=re.I)
     return (int(m.group(1)), f"{TRAFFIC_FILE}@{c.group(1) if c else 'unknown'}") if m else (None, None)
 
 
