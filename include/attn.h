@@ -58,8 +58,8 @@ enum {
  * the current device (all of its LDS), each working through a list of such
  * items -- or, when those items would occupy at most a quarter of the compute
  * units (few query rows, however long the key sequence), with one workgroup per
- * 32 query rows of one query head, whose wavefronts share the item's keys and
- * merge their partial results through LDS.  Either way nothing is allocated.
+ * 32 query rows that share a K/V head (p heads x 32/p positions), whose
+ * wavefronts share the item's keys and merge their partial results through LDS.  Either way nothing is allocated.
  * The first call on a device queries the device once and sets function
  * attributes, so make one ordinary call on a device before recording attn_fwd
  * into a HIP graph (later calls are one kernel launch and nothing else, and

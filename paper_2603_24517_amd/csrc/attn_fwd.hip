@@ -1065,8 +1065,9 @@ void attn_fwd_kernel(const Params p)
 // ---------------------------------------------------------------------------------------------------
 // The kernel for small problems.  With 256 query rows per work item a short query sequence (or few
 // heads) leaves most compute units without work, however long the key sequence is.  Here a work item
-// is 32 query rows of one query head, and the eight wavefronts of the workgroup share its KEYS instead
-// of its rows: wavefront w takes the 32-key blocks w, w + 8, ... with a running maximum and running
+// is 32 query rows that share a K/V head -- PACK query heads of one group x 32/PACK positions, so that
+// grouped-query heads share the K/V blocks here too -- and the eight wavefronts of the workgroup share its
+// KEYS instead of its rows: wavefront w takes the 32-key blocks w, w + 8, ... with a running maximum and running
 // sums of its own (the same online softmax, paper section 2.2), staging its K and V blocks through a
 // private 16 KiB of LDS, and the eight partial results are merged through LDS at the end:
 //     M = max_w m_w,  f_w = 2^(m_w - M),  O = sum_w f_w acc_w / sum_w f_w lr_w,  LSE = ln2 (M + log2 sum_w f_w l_w).
@@ -1076,8 +1077,11 @@ struct SplitParams {
     __bf16 *o;
     float *lse;
     int Hq, Hkv, Sq, Skv, G;
-    int ntile;      // ceil(Sq / 32)
-    float c;        // scale * log2(e)
+    int pack, pack_log2;    // query heads of one K/V group in a work item (8, 4, 2 or 1); row r is head r % pack, position r / pack
+    int chunks;             // G / pack
+    int tile_pos;           // query positions per work item = 32 / pack
+    int ntile;              // ceil(Sq / tile_pos)
+    float c;                // scale * log2(e)
 };
 constexpr int SPLIT_KEYS = 32;                                  // keys per block of the split kernel
 constexpr int SPLIT_TILE_BYTES = SPLIT_KEYS * ROW_BYTES;        // 8 KiB: one K or V block
@@ -1100,14 +1104,17 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_split_kernel(const SplitPar
 #ifdef ATTN_CLOCKS
     if (item == 0 && tid == 0) { g_clocks[2] = wall_clock64(); g_clocks[0] = __builtin_readcyclecounter(); }
 #endif
-    const int tile = item % p.ntile, bh = item / p.ntile;
-    const int head = bh % p.Hq, b = bh / p.Hq;
-    const int hkv = head / p.G;
-    const int q0 = tile * 32;
+    const int tile = item % p.ntile, rest = item / p.ntile;
+    const int chunk = rest % p.chunks, bh = rest / p.chunks;
+    const int hkv = bh % p.Hkv, b = bh / p.Hkv;
+    const int q0 = tile * p.tile_pos;
+    // this lane's query: head and position (rows past the end of Q compute on the last row and are not stored)
+    const int head = hkv * p.G + chunk * p.pack + (l32 & (p.pack - 1));
+    const int qpos = q0 + (l32 >> p.pack_log2);
     const int off = p.Skv - p.Sq;
     // keys 0 .. klast are valid for some row of the tile
     int klast = p.Skv - 1;
-    if (CAUSAL) klast = min(klast, min(q0 + 31, p.Sq - 1) + off);
+    if (CAUSAL) klast = min(klast, min(q0 + p.tile_pos - 1, p.Sq - 1) + off);
     const int nb = klast < 0 ? 0 : klast / SPLIT_KEYS + 1;
     const size_t kv_row_bytes = (size_t)p.Hkv * HD * 2;
     const unsigned char *kg = (const unsigned char *)(p.k + ((size_t)b * p.Skv * p.Hkv + hkv) * HD);
@@ -1116,7 +1123,7 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_split_kernel(const SplitPar
     // Q^T operand, straight from global memory (rows past the end re-read the last row)
     bf16x8 qf[8];
     {
-        const int qrow = min(q0 + l32, p.Sq - 1);
+        const int qrow = min(qpos, p.Sq - 1);
         const __bf16 *qp = p.q + ((size_t)((size_t)b * p.Sq + qrow) * p.Hq + head) * HD + 8 * hh;
 #pragma unroll
         for (int s = 0; s < 8; ++s) qf[s] = *(const bf16x8 *)(qp + 16 * s);
@@ -1193,7 +1200,7 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_split_kernel(const SplitPar
         if (more) request(t + NWAVES, false);
         // exact online softmax of the block, masked per key
         int lim = p.Skv - 1;
-        if (CAUSAL) lim = min(lim, q0 + l32 + off);
+        if (CAUSAL) lim = min(lim, qpos + off);
         const int kidx = t * SPLIT_KEYS + 4 * hh;
         constexpr float NONE = NEG ? INFINITY : -INFINITY;
         float mx = NONE;
@@ -1304,13 +1311,13 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_split_kernel(const SplitPar
             }
         }
         const float inv = LR > 0.0f ? 1.0f / LR : 0.0f;
-        if (q0 + l32 < p.Sq) {
+        if (qpos < p.Sq) {
             u32x4 ww = {pack_bf16(o8[0] * inv, o8[1] * inv), pack_bf16(o8[2] * inv, o8[3] * inv),
                         pack_bf16(o8[4] * inv, o8[5] * inv), pack_bf16(o8[6] * inv, o8[7] * inv)};
-            __bf16 *op = p.o + ((size_t)((size_t)b * p.Sq + q0 + l32) * p.Hq + head) * HD + 16 * wave + 8 * hh;
+            __bf16 *op = p.o + ((size_t)((size_t)b * p.Sq + qpos) * p.Hq + head) * HD + 16 * wave + 8 * hh;
             *(u32x4 *)op = ww;
             if (wave == 0 && hh == 0)
-                p.lse[((size_t)b * p.Hq + head) * p.Sq + q0 + l32] =
+                p.lse[((size_t)b * p.Hq + head) * p.Sq + qpos] =
                     L > 0.0f ? (M + __builtin_amdgcn_logf(L)) * 0.6931471805599453f : -INFINITY;
         }
     }
@@ -1392,13 +1399,16 @@ int attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
 
     // Small problems: few 256-row items would leave most compute units idle; 32-row items whose keys
     // are shared out among the wavefronts of a workgroup fill the device instead.
-    const int64_t split_items = (int64_t)B * Hq * ((Sq + 31) / 32);
+    const int split_tile_pos = 32 / sh.pack;
+    const int64_t split_items = (int64_t)B * Hkv * sh.chunks * ((Sq + split_tile_pos - 1) / split_tile_pos);
     const bool small = ATTN_SMALL_PATH == 2 || (ATTN_SMALL_PATH == 1 && total * 4 <= ncu);
     if (small && split_items < INT32_MAX) {
         SplitParams sp = {};
         sp.q = p.q; sp.k = p.k; sp.v = p.v; sp.o = p.o; sp.lse = lse;
         sp.Hq = Hq; sp.Hkv = Hkv; sp.Sq = Sq; sp.Skv = Skv; sp.G = sh.G;
-        sp.ntile = (Sq + 31) / 32;
+        sp.pack = sh.pack; sp.pack_log2 = sh.pack_log2; sp.chunks = sh.chunks;
+        sp.tile_pos = split_tile_pos;
+        sp.ntile = (Sq + split_tile_pos - 1) / split_tile_pos;
         sp.c = p.c;
         const dim3 sgrid((unsigned)split_items), sblock(NTHREADS);
         if (causal && neg)
