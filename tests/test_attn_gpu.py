@@ -119,8 +119,13 @@ def test_split_merge_gpu():
     assert np.abs(o - (w1 * o1 + w2 * o2)).max() <= 2e-2
 
 
-def test_deterministic_and_stream_gpu():
-    q, k, v = U.rand_qkv(2, 4, 2, 333, 333, seed=26)
+# (B, Hq, Hkv, Sq, Skv): one launch that goes to the split-key kernel (few rows) and one that goes to the 256-row kernel
+BOTH_KERNELS = [(2, 4, 2, 333, 333), (4, 16, 4, 1000, 1100)]
+
+
+@pytest.mark.parametrize("shape", BOTH_KERNELS, ids=["split_key_kernel", "main_kernel"])
+def test_deterministic_and_stream_gpu(shape):
+    q, k, v = U.rand_qkv(*shape, seed=26)
     o1, l1 = U.run_gpu(q, k, v, True, SCALE)
     s = torch.cuda.Stream()
     with torch.cuda.stream(s):
@@ -128,11 +133,12 @@ def test_deterministic_and_stream_gpu():
     assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
 
 
-def test_launch_recorded_in_a_hip_graph_replays_identically():
+@pytest.mark.parametrize("shape", [(2, 8, 2, 700, 900), (4, 16, 4, 1000, 1100)], ids=["split_key_kernel", "main_kernel"])
+def test_launch_recorded_in_a_hip_graph_replays_identically(shape):
     """attn_fwd only enqueues one kernel, so (after one ordinary call on the device) it can be recorded
     into a HIP graph; every replay, with other work and synchronisations in between, must reproduce the
     directly launched result bit for bit."""
-    B, Hq, Hkv, Sq, Skv = 2, 8, 2, 700, 900
+    B, Hq, Hkv, Sq, Skv = shape
     q, k, v = U.rand_qkv(B, Hq, Hkv, Sq, Skv, seed=28)
     o_ref, lse_ref = U.run_gpu(q, k, v, True, SCALE)            # also the first call on the device
     dev = torch.device("cuda:0")
