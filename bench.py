@@ -102,6 +102,20 @@ def kernel_clock(w, qd, kd, vd, o, lse, launches=40):
     return P.clocks_read()
 
 
+def item_phases(w, qd, kd, vd, o, lse, launches=10):
+    """One wavefront's cycles through the phases of a work item (variants/libattn_phases.so: set-up, first score
+    blocks, first softmax, iterations by kind, epilogue), for the first and the last wavefront of the first
+    workgroup; None where the split-key kernel runs or a workgroup has fewer than two items."""
+    from paper_2603_24517_amd import probe as P
+    stream = torch.cuda.current_stream()
+    for _ in range(launches):
+        rc = P.variant_attn_fwd("phases", qd, kd, vd, o, lse, w.B, w.Hq, w.Hkv, w.Sq, w.Skv, w.D, w.causal, w.scale,
+                                stream.cuda_stream)
+        if rc != 0:
+            raise A.AttnError(rc)
+    return P.phases_read()
+
+
 TRAFFIC_FILE = "profiles/attn_fwd_kernel_hbm_traffic.md"
 
 
@@ -227,6 +241,8 @@ def run_workload(name, steps, warmup, with_cpu, repeats=1, variant=None):
     if with_cpu:
         out["cpu_baseline"], out["parity"] = cpu_baseline(w, q, k, v, o, lse)
         out["roofline"].update(kernel_clock(w, qd, kd, vd, o, lse))
+        if out["roofline"]["kernel"] == "attn_fwd_kernel":
+            out["roofline"]["item_phases_cycles"] = item_phases(w, qd, kd, vd, o, lse)
         out["mfma_probe"] = mfma_probe()
         ceiling = out["mfma_probe"]["ceiling"]["tflops"]
         out["roofline"]["frac_of_probe_ceiling"] = ktflops / ceiling

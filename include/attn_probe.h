@@ -76,6 +76,27 @@ int attn_probe_device_info(int *compute_units, int *clock_khz);
  */
 int attn_clocks_read(unsigned long long *out);
 
+/*
+ * attn_phases_read -- exported only by the build of the attention library with -DATTN_CLOCKS=2
+ * (paper_2603_24517_amd/variants/libattn_phases.so, which exports attn_clocks_read too).  Waits for
+ * the device, then copies what two wavefronts of the first workgroup of the last attn_fwd launch
+ * (256-row kernel) added up over that workgroup's SECOND work item: shader cycles per phase of the
+ * item as that wavefront went through it.  One wavefront's latencies, not the workgroup's
+ * throughput: the other wavefront of its SIMD fills many of the gaps.
+ *   out[0..11]   first wavefront:  0 set-up (lookup of the next item, state reset, Q request; for an
+ *                item whose tiles were not requested ahead also those requests and their wait),
+ *                1 the first two score products, 2 the first softmax, 3 the barrier and the tile
+ *                requests before the loop, 4 iterations this wavefront ran on the fast path (no
+ *                mask, in-loop requests), 5 their number, 6 the other iterations except the last,
+ *                7 their number, 8 the last iteration (PV only), 9 the wait for outstanding loads,
+ *                10 the epilogue, 11 the whole item
+ *   out[12..23]  the same for the last wavefront
+ *   out  out  host, 24 x 64-bit (zero or stale if that workgroup had fewer than two items)
+ * A stamp per iteration lengthens the loop by about 1.5 %.
+ * Returns 0, or a negative ATTN_E_* code of include/attn.h.
+ */
+int attn_phases_read(unsigned long long *out);
+
 #ifdef __cplusplus
 }
 #endif

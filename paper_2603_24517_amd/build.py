@@ -38,6 +38,8 @@ VARIANTS = {
     "lds_prefetch_5": ["-DATTN_LDS_PREFETCH=5"],
     # the shipped kernel plus clock stamps of its first workgroup (exports attn_clocks_read as well)
     "clocks": ["-DATTN_CLOCKS"],
+    # the same plus cycle sums per phase of one work item (exports attn_phases_read as well)
+    "phases": ["-DATTN_CLOCKS=2"],
 }
 
 

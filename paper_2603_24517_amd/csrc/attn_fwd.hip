@@ -99,6 +99,10 @@
 // counter where the key-block loop of its second and of its third work item starts and ends; the
 // library exports attn_clocks_read(), and the benchmark derives the shader clock of a launch, the
 // length of an iteration and the stretch between two items from the stamps.
+// ATTN_CLOCKS=2 additionally has the first and the last wavefront of that workgroup add up, over its
+// second work item, the cycles each phase of an item takes (set-up, first score blocks, first softmax,
+// the key-block iterations by kind, epilogue), read with attn_phases_read().  A stamp per iteration
+// costs about 1.5 % of the loop, which is why the clock figures come from the build without them.
 static_assert(ATTN_SOFTMAX >= 0 && ATTN_SOFTMAX <= 3, "ATTN_SOFTMAX is 0, 1, 2 or 3");
 static_assert(ATTN_LDS_PREFETCH >= 1 && ATTN_LDS_PREFETCH <= 8, "ATTN_LDS_PREFETCH is 1 .. 8");
 
@@ -278,6 +282,26 @@ __device__ unsigned long long g_clocks[10];
                                   g_clocks[4 + 3 * (item_no - 1) + (k)] = (v); __builtin_amdgcn_sched_barrier(0); } while (0)
 #else
 #define ATTN_STAMP(k, v) do { } while (0)
+#endif
+#if defined(ATTN_CLOCKS) && ATTN_CLOCKS >= 2
+// [first / last wavefront of the first workgroup][phase]: cycles of its second work item spent in
+// 0 set-up (next item's lookup, state reset, Q request; a cold item's first tile requests and wait),
+// 1 the first two score blocks, 2 the first softmax, 3 the barrier and requests before the loop,
+// 4 iterations in which this wavefront took the fast path, 5 their number, 6 other iterations but the
+// last, 7 their number, 8 the last iteration, 9 the wait for outstanding loads, 10 the epilogue,
+// 11 the whole item
+__device__ unsigned long long g_phases[2][12];
+__device__ __forceinline__ unsigned long long phase_now() {
+    __builtin_amdgcn_sched_barrier(0);
+    const unsigned long long t = __builtin_readcyclecounter();
+    __builtin_amdgcn_sched_barrier(0);
+    return t;
+}
+#define ATTN_PHASE(k) do { const unsigned long long now_ = phase_now(); ph[k] += now_ - ph_prev; ph_prev = now_; } while (0)
+#define ATTN_PHASE_COUNT(k) do { ++ph[k]; } while (0)
+#else
+#define ATTN_PHASE(k) do { } while (0)
+#define ATTN_PHASE_COUNT(k) do { } while (0)
 #endif
 
 template <bool CAUSAL, bool NEG>
@@ -836,7 +860,15 @@ void attn_fwd_kernel(const Params p)
 #ifdef ATTN_CLOCKS
     int item_no = 0;
 #endif
+#if defined(ATTN_CLOCKS) && ATTN_CLOCKS >= 2
+    unsigned long long ph[11], ph_prev = 0, ph_item = 0;
+#endif
     while (have) {
+#if defined(ATTN_CLOCKS) && ATTN_CLOCKS >= 2
+#pragma unroll
+        for (int k = 0; k < 11; ++k) ph[k] = 0;
+        ph_prev = ph_item = phase_now();
+#endif
         enter(cur);
         reset_state();
         // the item after this one
@@ -868,8 +900,10 @@ void attn_fwd_kernel(const Params p)
                 wg_barrier();
             }
             // warm: K(0), K(1) landed before the last barrier of the item before, and Q is in registers
+            ATTN_PHASE(0);
             qk_only(sa, stage_off(0));
             qk_only(sb, stage_off(1));
+            ATTN_PHASE(1);
             // P(0).  A first block without masked keys (every one but a causal item's diagonal start or a
             // short tail) takes its maximum as the reference and has nothing to rescale yet; the masked
             // path also handles an empty first block.
@@ -879,6 +913,7 @@ void attn_fwd_kernel(const Params p)
             } else {
                 softmax_masked(sa, 0);
             }
+            ATTN_PHASE(2);
             // K(2), V(0) landed: a warm item waited for them before the epilogue of the item before, and
             // what it still has in flight are that epilogue's stores, which nothing here depends on
             if (!warm) __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
@@ -893,6 +928,7 @@ void attn_fwd_kernel(const Params p)
             // receives S(j+2).
             int j = 0;
             ATTN_STAMP(0, __builtin_readcyclecounter());
+            ATTN_PHASE(3);
             // Iterations j < fast_end take the fast path: S(j+1) needs no mask, and the tiles requested are
             // full ones (past the last block: of the next item, or the last block again).
             int fast_end = all_full ? n_unm - 1 : min(n_unm - 1, nfull - (2 + REQ_AHEAD));
@@ -925,6 +961,8 @@ void attn_fwd_kernel(const Params p)
                 ATTN_ADVANCE_REQUESTS();                                                     \
                 __builtin_amdgcn_s_waitcnt(WAIT_ITER_END);                                   \
                 wg_barrier();                                                                \
+                ATTN_PHASE(4);                                                               \
+                ATTN_PHASE_COUNT(5);                                                         \
             } while (0)
             // The bulk of the fast iterations runs in a loop unrolled six times (two score buffers x three
             // stages), in which every LDS address is a register plus a constant.  That loop wants block j in
@@ -971,6 +1009,12 @@ void attn_fwd_kernel(const Params p)
                 }
                 __builtin_amdgcn_s_waitcnt(WAIT_ITER_END);
                 wg_barrier();
+                if (jj == nblk - 1) {
+                    ATTN_PHASE(8);
+                } else {
+                    ATTN_PHASE(6);
+                    ATTN_PHASE_COUNT(7);
+                }
             };
 #pragma nounroll
             for (; j < nblk - 1; j += 2) {
@@ -991,6 +1035,7 @@ void attn_fwd_kernel(const Params p)
         // waited for here, before the epilogue's stores join the queue, so that its first barrier can
         // publish them.
         __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
+        ATTN_PHASE(9);
 
         // ---- Q of the next item into registers, from this wavefront's LDS region
         if (ATTN_ITEM_OVERLAP && have2) {
@@ -1048,6 +1093,14 @@ void attn_fwd_kernel(const Params p)
         }
 
         if (!ATTN_ITEM_OVERLAP && have2) load_q(nxt);
+#if defined(ATTN_CLOCKS) && ATTN_CLOCKS >= 2
+        ATTN_PHASE(10);
+        if (bid == 0 && item_no == 1 && (tid == 0 || tid == NTHREADS - 64)) {
+#pragma unroll
+            for (int k = 0; k < 11; ++k) g_phases[tid != 0][k] = ph[k];
+            g_phases[tid != 0][11] = ph_prev - ph_item;
+        }
+#endif
 #ifdef ATTN_CLOCKS
         ++item_no;
 #endif
@@ -1475,6 +1528,14 @@ int attn_clocks_read(unsigned long long *out)
     if (!out) return ATTN_E_NULL;
     return hipMemcpyFromSymbol(out, HIP_SYMBOL(g_clocks), sizeof(g_clocks)) == hipSuccess ? ATTN_OK : ATTN_E_LAUNCH;
 }
+#if ATTN_CLOCKS >= 2
+// Waits for the device, then copies the phase sums of the last launch to the host (2 x 12 x 64-bit).
+int attn_phases_read(unsigned long long *out)
+{
+    if (!out) return ATTN_E_NULL;
+    return hipMemcpyFromSymbol(out, HIP_SYMBOL(g_phases), sizeof(g_phases)) == hipSuccess ? ATTN_OK : ATTN_E_LAUNCH;
+}
+#endif
 #endif
 
 }  // extern "C"

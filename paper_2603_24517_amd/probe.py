@@ -59,9 +59,12 @@ def load_variant(name):
         raise KeyError(f"unknown variant {name!r}; known: {sorted(VARIANTS)}")
     if name not in _variants:
         lib = open_library(variant_path(name))
-        if name == "clocks":
+        if name in ("clocks", "phases"):
             lib.attn_clocks_read.argtypes = [ctypes.POINTER(ctypes.c_ulonglong)]
             lib.attn_clocks_read.restype = ctypes.c_int
+        if name == "phases":
+            lib.attn_phases_read.argtypes = [ctypes.POINTER(ctypes.c_ulonglong)]
+            lib.attn_phases_read.restype = ctypes.c_int
         _variants[name] = lib
     return _variants[name]
 
@@ -87,4 +90,26 @@ def clocks_read():
         res["cycles_per_iteration"] = (e3 - s3) / n3
         res["cycles_between_items"] = s3 - e2
         res["iterations_per_item"] = n3
+    return res
+
+
+PHASES = ("setup", "first_two_score_blocks", "first_softmax", "barrier_and_first_requests", "fast_iterations",
+          "fast_iterations_n", "other_iterations", "other_iterations_n", "last_iteration", "wait_for_loads", "epilogue",
+          "item")
+
+
+def phases_read():
+    """Cycle sums per phase of the second work item of the first workgroup in the last launch of the `phases`
+    variant: {"first_wavefront": {phase: cycles}, "last_wavefront": {...}}, or None if that workgroup had fewer
+    than two items (or took the split-key kernel).  Waits for the device."""
+    out = (ctypes.c_ulonglong * 24)()
+    rc = load_variant("phases").attn_phases_read(out)
+    if rc != 0:
+        raise RuntimeError(f"attn_phases_read failed ({rc})")
+    res = {}
+    for w, name in enumerate(("first_wavefront", "last_wavefront")):
+        v = [int(out[12 * w + k]) for k in range(12)]
+        if v[11] == 0 or sum(v[k] for k in (0, 1, 2, 3, 4, 6, 8, 9, 10)) != v[11]:     # nothing written, or torn
+            return None
+        res[name] = dict(zip(PHASES, v))
     return res

@@ -37,13 +37,15 @@ def test_header_symbols_exported():
 def test_probe_header_symbols_exported():
     from paper_2603_24517_amd import build as B
     syms = _declared_symbols("attn_probe.h")
-    assert syms == ["attn_clocks_read", "attn_probe_device_info", "attn_probe_mfma"]
+    assert syms == ["attn_clocks_read", "attn_phases_read", "attn_probe_device_info", "attn_probe_mfma"]
     assert _exported_symbols(B.PROBE_LIB) == ["attn_probe_device_info", "attn_probe_mfma"]
-    # every variant build keeps the C ABI of include/attn.h; the clocks build adds its reader
+    # every variant build keeps the C ABI of include/attn.h; the clocks and phases builds add their readers
     for name in B.VARIANTS:
         want = ["attn_fwd", "attn_strerror", "attn_version"]
-        if name == "clocks":
+        if name in ("clocks", "phases"):
             want = ["attn_clocks_read"] + want
+        if name == "phases":
+            want = ["attn_phases_read"] + want
         assert _exported_symbols(B.variant_path(name)) == sorted(want), name
 
 

@@ -127,6 +127,33 @@ def test_clocks_variant_reports_a_plausible_clock():
     assert 1000 < c["cycles_between_items"] < 60000
 
 
+def test_phases_variant_accounts_for_every_cycle_of_an_item():
+    w = W.WORKLOADS["cfg3a_mha_c_b8_s4096_q4"]
+    q, k, v = (x.cuda() for x in W.make_qkv(w))
+    o = torch.empty_like(q)
+    lse = torch.empty((w.B, w.Hq, w.Sq), dtype=torch.float32, device="cuda")
+    for _ in range(3):
+        assert P.variant_attn_fwd("phases", q, k, v, o, lse, w.B, w.Hq, w.Hkv, w.Sq, w.Skv, w.D, True, w.scale,
+                                  torch.cuda.current_stream().cuda_stream) == 0
+    ph = P.phases_read()
+    print(ph, flush=True)
+    assert ph is not None
+    for wave in ("first_wavefront", "last_wavefront"):
+        d = ph[wave]
+        # a 256-row item of this workload has 4 .. 64 key blocks: iterations 0 .. nblk-2 are counted by kind, then the last
+        n = d["fast_iterations_n"] + d["other_iterations_n"] + 1
+        assert 4 <= n <= 64 and n % 4 == 0, d
+        assert d["item"] == sum(d[key] for key in ("setup", "first_two_score_blocks", "first_softmax", "barrier_and_first_requests",
+                                                  "fast_iterations", "other_iterations", "last_iteration", "wait_for_loads",
+                                                  "epilogue"))
+        # two score products are 32 MFMAs of 32 matrix-pipe cycles; an iteration of either kind holds 32 as well
+        assert d["first_two_score_blocks"] >= 1024 and d["epilogue"] > 0 and d["last_iteration"] >= 512
+        iters = d["fast_iterations"] + d["other_iterations"]
+        assert 1024 * (n - 1) <= iters < 8000 * (n - 1), d
+    # the first wavefront's rows end before the diagonal blocks of the last: it runs fewer fast iterations or as many
+    assert ph["first_wavefront"]["fast_iterations_n"] <= ph["last_wavefront"]["fast_iterations_n"]
+
+
 @pytest.mark.parametrize("waves", [1, 2, 4])
 @pytest.mark.parametrize("mode", range(8))
 def test_probe_runs(mode, waves):
