@@ -1134,13 +1134,16 @@ struct SplitParams {
     int chunks;             // G / pack
     int tile_pos;           // query positions per work item = 32 / pack
     int ntile;              // ceil(Sq / tile_pos)
+    Div d_ntile, d_chunks, d_hkv;   // exact division by ntile, chunks, Hkv
     float c;                // scale * log2(e)
 };
 constexpr int SPLIT_KEYS = 32;                                  // keys per block of the split kernel
 constexpr int SPLIT_TILE_BYTES = SPLIT_KEYS * ROW_BYTES;        // 8 KiB: one K or V block
 constexpr int SPLIT_WAVE_BYTES = 2 * SPLIT_TILE_BYTES;          // per wavefront: its K block, then its V block
 constexpr int SPLIT_STATE_BASE = NWAVES * SPLIT_WAVE_BYTES;     // after them: m, l, lr of every wavefront
-constexpr int SPLIT_LDS_BYTES = SPLIT_STATE_BASE + NWAVES * 3 * 32 * 4;
+constexpr int SPLIT_Q_BASE = SPLIT_STATE_BASE + NWAVES * 3 * 32 * 4;   // then the item's 32 Q rows (K's swizzle)
+constexpr int SPLIT_LDS_BYTES = SPLIT_Q_BASE + 32 * ROW_BYTES;
+static_assert(SPLIT_Q_BASE % 1024 == 0 && NWAVES * 4 == 32, "each wavefront requests four of the 32 Q rows, 1 KiB");
 static_assert(SPLIT_WAVE_BYTES == 32 * HD * 4, "a wavefront's partial accumulator takes the place of its two blocks");
 static_assert(SPLIT_LDS_BYTES <= LDS_BYTES, "the split kernel is launched with the same dynamic LDS size");
 
@@ -1157,9 +1160,9 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_split_kernel(const SplitPar
 #ifdef ATTN_CLOCKS
     if (item == 0 && tid == 0) { g_clocks[2] = wall_clock64(); g_clocks[0] = __builtin_readcyclecounter(); }
 #endif
-    const int tile = item % p.ntile, rest = item / p.ntile;
-    const int chunk = rest % p.chunks, bh = rest / p.chunks;
-    const int hkv = bh % p.Hkv, b = bh / p.Hkv;
+    const int rest = fast_div(item, p.d_ntile), tile = item - rest * p.ntile;
+    const int bh = fast_div(rest, p.d_chunks), chunk = rest - bh * p.chunks;
+    const int b = fast_div(bh, p.d_hkv), hkv = bh - b * p.Hkv;
     const int q0 = tile * p.tile_pos;
     // this lane's query: head and position (rows past the end of Q compute on the last row and are not stored)
     const int head = hkv * p.G + chunk * p.pack + (l32 & (p.pack - 1));
@@ -1172,21 +1175,6 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_split_kernel(const SplitPar
     const size_t kv_row_bytes = (size_t)p.Hkv * HD * 2;
     const unsigned char *kg = (const unsigned char *)(p.k + ((size_t)b * p.Skv * p.Hkv + hkv) * HD);
     const unsigned char *vg = (const unsigned char *)(p.v + ((size_t)b * p.Skv * p.Hkv + hkv) * HD);
-
-    // Q^T operand, straight from global memory (rows past the end re-read the last row)
-    bf16x8 qf[8];
-    {
-        const int qrow = min(qpos, p.Sq - 1);
-        const __bf16 *qp = p.q + ((size_t)((size_t)b * p.Sq + qrow) * p.Hq + head) * HD + 8 * hh;
-#pragma unroll
-        for (int s = 0; s < 8; ++s) qf[s] = *(const bf16x8 *)(qp + 16 * s);
-    }
-    f32x16 acc[4];
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[dt][r] = 0.0f;
-    float m = -INFINITY, l = 0.0f, lr = 0.0f;
 
     const uint32_t kbase = wave * SPLIT_WAVE_BYTES, vbase = kbase + SPLIT_TILE_BYTES;
     const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
@@ -1215,6 +1203,34 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_split_kernel(const SplitPar
             }
         }
     };
+    // What the first MFMA needs goes out first, and before anything else is computed: the eight wavefronts'
+    // first blocks are 128 KiB through a load path of 64 bytes a clock, the longest single stretch of a
+    // small launch.  The item's 32 Q rows go through LDS as well, each wavefront requesting four of them
+    // (rows past the end re-read the last row): fetched by every wavefront for itself they would be
+    // another 64 KiB on that path, and as ordinary loads they would make the compiler's own count of
+    // outstanding loads, which knows nothing of the requests around them, wait for V before the first MFMA.
+    {
+        const int r = 4 * wave + (lane >> 4), unit = lane & 15;
+        const int row0 = min(q0, p.Sq - 1);
+        const int drow = min(q0 + (r >> p.pack_log2), p.Sq - 1) - row0;         // 0 .. 31
+        const int dhead = r & (p.pack - 1);
+        const unsigned char *qg = (const unsigned char *)(p.q + ((size_t)((size_t)b * p.Sq + row0) * p.Hq + hkv * p.G + chunk * p.pack) * HD);
+        // (at most 32 rows of at most 32768 heads of 256 bytes: the offset fits 32 bits)
+        const uint32_t o = (uint32_t)(drow * p.Hq + dhead) * (uint32_t)(HD * 2) + ((unit ^ (r & 15)) << 4);
+        lds_dma16(qg, o, lds0 + SPLIT_Q_BASE + wave * 1024);
+    }
+    int t = wave;
+    if (t < nb) {
+        request(t, false);
+        request(t, true);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    f32x16 acc[4];
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[dt][r] = 0.0f;
+    float m = -INFINITY, l = 0.0f, lr = 0.0f;
     int kaddr[8];
 #pragma unroll
     for (int st = 0; st < 8; ++st) kaddr[st] = kbase + l32 * ROW_BYTES + (((2 * st + hh) ^ (l32 & 15)) << 4);
@@ -1229,14 +1245,18 @@ __global__ __launch_bounds__(NTHREADS) void attn_fwd_split_kernel(const SplitPar
         }
     }
 
-    // Blocks wave, wave + 8, ...: K(t) and V(t) are requested ahead; K(t + 8) goes out as soon as the
+    // this wavefront's Q rows have landed (and K(t), if it has a block: both are older than V(t)'s
+    // eight requests); the barrier publishes all 32 rows
+    if (t < nb) __builtin_amdgcn_s_waitcnt(wait_vmcnt(8)); else __builtin_amdgcn_s_waitcnt(WAIT_VMCNT0);
+    wg_barrier();
+    bf16x8 qf[8];           // Q^T operand: query l32, d = 16 s + 8 hh .. + 7
+#pragma unroll
+    for (int s = 0; s < 8; ++s)
+        qf[s] = *(const LDS_AS bf16x8 *)(lds + SPLIT_Q_BASE + l32 * ROW_BYTES + (((2 * s + hh) ^ (l32 & 15)) << 4));
+
+    // Blocks wave, wave + 8, ...: K(t) and V(t) were requested above (this wavefront's first block); K(t + 8) goes out as soon as the
     // score MFMAs have read K(t), V(t + 8) as soon as the PV MFMAs have read V(t), so that a wait is "all
     // but the newest eight requests have landed" while there is a next block and "all" at the last one.
-    int t = wave;
-    if (t < nb) {
-        request(t, false);
-        request(t, true);
-    }
     for (; t < nb; t += NWAVES) {
         const bool more = t + NWAVES < nb;
         __builtin_amdgcn_s_waitcnt(wait_vmcnt(8));          // K(t) has landed
@@ -1462,6 +1482,9 @@ int attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
         sp.pack = sh.pack; sp.pack_log2 = sh.pack_log2; sp.chunks = sh.chunks;
         sp.tile_pos = split_tile_pos;
         sp.ntile = (Sq + split_tile_pos - 1) / split_tile_pos;
+        sp.d_ntile = make_div((uint32_t)sp.ntile);
+        sp.d_chunks = make_div((uint32_t)sp.chunks);
+        sp.d_hkv = make_div((uint32_t)Hkv);
         sp.c = p.c;
         const dim3 sgrid((unsigned)split_items), sblock(NTHREADS);
         if (causal && neg)
